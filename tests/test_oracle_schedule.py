@@ -1,0 +1,175 @@
+"""Pins for the schedule oracle: the V map, direction split, conflict-freeness, the closed
+forms the paper prints for the basic unit, dependency validity, and hop counts."""
+import random
+from fractions import Fraction
+
+import pytest
+
+from oracle import schedule_oracle as so
+
+
+def _golden_rows():
+    import os
+    p = os.path.join(os.path.dirname(__file__), "golden", "paper_bitpipe_closed_forms.txt")
+    rows = []
+    for line in open(p):
+        line = line.strip()
+        if not line or line.startswith("#") or line.startswith("EF"):
+            continue
+        rows.append([float(v) for v in line.split()])
+    return rows
+
+
+def test_vmap_matches_section_3_2_example():
+    # D = 2: stages 1..2 on P1..P2, stages 3..4 on P2..P1
+    assert [so.vmap(0, s, 2) for s in range(4)] == [0, 1, 1, 0]
+    # D = 4 down: stages 1..4 -> P1..P4, 5..8 -> P4..P1; up is the mirror image
+    assert [so.vmap(0, s, 4) for s in range(8)] == [0, 1, 2, 3, 3, 2, 1, 0]
+    assert [so.vmap(1, s, 4) for s in range(8)] == [3, 2, 1, 0, 0, 1, 2, 3]
+
+
+@pytest.mark.parametrize("D", [2, 4, 6, 8])
+def test_vmap_properties(D):
+    for dr in (0, 1):
+        devs = [so.vmap(dr, s, D) for s in range(2 * D)]
+        # every device holds exactly two chunks per direction; the turn is a local copy
+        assert sorted(devs) == sorted(list(range(D)) * 2)
+        assert devs[D - 1] == devs[D]
+        # every other hop goes to a neighbouring device
+        for s in range(1, 2 * D):
+            if s != D:
+                assert abs(devs[s] - devs[s - 1]) == 1
+    # the two replicas of a stage sit on devices d and D-1-d
+    for s in range(2 * D):
+        assert so.vmap(0, s, D) + so.vmap(1, s, D) == D - 1
+
+
+@pytest.mark.parametrize("D,N", [(2, 2), (4, 4), (4, 8), (6, 6), (4, 16)])
+def test_direction_split_half_and_half(D, N):
+    dirs = [so.direction_of(m, D) for m in range(N)]
+    assert dirs.count(0) == dirs.count(1) == N // 2
+    for u in range(N // D):
+        assert dirs[u * D:u * D + D // 2] == [0] * (D // 2)
+        assert dirs[u * D + D // 2:(u + 1) * D] == [1] * (D // 2)
+
+
+@pytest.mark.parametrize("D,N", [(2, 2), (2, 4), (4, 4), (4, 8), (4, 16), (6, 6), (6, 12), (8, 8)])
+def test_generated_order_is_valid_and_conflict_free(D, N):
+    lanes = so.generate_timeline(D, N)
+    assert so.conflicts(lanes) == 0
+    order = so.serialise(lanes)
+    assert len(order) == 2 * 2 * D * N
+    assert so.validate(order, D, N) is None
+    # exactly one F and one B per (stage, mb)
+    assert len({(o.kind, o.stage, o.mb) for o in order}) == len(order)
+    # never more than 2D chunk stashes (= D stage-activations) on a device
+    assert max(so.peak_stash(lanes)) <= 2 * D
+    # every device does the same amount of work: 2 chunks/direction * N/2 mbs * 2 directions
+    for lane in lanes:
+        assert sum(sl.end - sl.start for sl in lane) == 3 * 2 * N
+
+
+def test_basic_unit_closed_forms_D4():
+    """Section 3.3 / Table 2 at D = 4, N = 4, read from the golden fixture."""
+    (D, N, fb, bb, num, den, lo, hi), = _golden_rows()
+    D, N = int(D), int(N)
+    lanes = so.generate_timeline(D, N)
+    ms = so.makespan(lanes)
+    # one device-forward = 2 chunk units; total time 3N + D - 2 device-forwards
+    assert ms == 2 * int(den) == 28
+    idle = so.idle_per_device(lanes)
+    assert all(Fraction(i, ms) == Fraction(int(num), int(den)) for i in idle)
+    # idle = (D-2)/2 forward bubbles + (D-2)/4 backward bubbles = 1*2 + 0.5*4 chunk units
+    assert all(i == int(fb * 2 + bb * 4) for i in idle)
+    # activations between (D+3)/2 and D stage-activations = 7..8 chunk stashes
+    peaks = so.peak_stash(lanes)
+    assert min(peaks) == int(lo * 2) and max(peaks) == int(hi * 2)
+    assert peaks == [7, 8, 8, 7]
+
+
+def test_concatenation_fills_tail_bubbles_D4():
+    """Section 3.5: N = 2D must beat two basic units back to back (56) and cannot beat the
+    closed form 2*(3N + D - 2) = 52; the greedy order lands at 53."""
+    ms = so.makespan(so.generate_timeline(4, 8))
+    assert 52 <= ms < 56
+    assert ms == 53
+
+
+def test_d2_has_no_bubbles():
+    # (D-2)/(3N+D-2) = 0 at D = 2
+    for N in (2, 4, 8):
+        lanes = so.generate_timeline(2, N)
+        assert so.idle_per_device(lanes) == [0, 0]
+
+
+def test_hops_per_pass():
+    # one pass over 2D stages: 2D-2 cross-device hops and one local copy (Section 3.2)
+    for D in (2, 4, 8):
+        hops, local = so.cross_device_hops(so.generate(D, D), D)
+        assert (hops, local) == (2 * D - 2, 1)
+    # whole iteration: forward and backward passes of N micro-batches -> 2N(2D-2) messages
+    D, N = 4, 8
+    order = so.generate(D, N)
+    msgs = 0
+    for o in order:
+        nxt = o.stage + 1 if o.kind == "F" else o.stage - 1
+        if 0 <= nxt < 2 * D and so.vmap(o.direction, nxt, D) != o.vdev:
+            msgs += 1
+    assert msgs == 2 * N * (2 * D - 2)
+
+
+def test_validator_rejects_planted_mistakes():
+    D, N = 4, 4
+    good = so.generate(D, N)
+    assert so.validate(good, D, N) is None
+    # drop an op
+    assert so.validate(good[:-1], D, N) is not None
+    # duplicate an op
+    assert so.validate(good + [good[0]], D, N) is not None
+    # swap a backward in front of its forward
+    i = next(k for k, o in enumerate(good) if o.kind == "B")
+    j = next(k for k, o in enumerate(good) if o.kind == "F" and (o.stage, o.mb) == (good[i].stage, good[i].mb))
+    bad = list(good)
+    bad[i], bad[j] = bad[j], bad[i]
+    assert so.validate(bad, D, N) is not None
+    # wrong device
+    bad = list(good)
+    bad[3] = bad[3]._replace(vdev=(bad[3].vdev + 1) % D)
+    assert so.validate(bad, D, N) is not None
+    # forward of stage s+1 before stage s
+    bad = [o for o in good]
+    k1 = next(k for k, o in enumerate(bad) if o.kind == "F" and o.stage == 1 and o.mb == 0)
+    k0 = next(k for k, o in enumerate(bad) if o.kind == "F" and o.stage == 0 and o.mb == 0)
+    bad[k0], bad[k1] = bad[k1], bad[k0]
+    assert so.validate(bad, D, N) is not None
+
+
+def test_random_topological_orders_validate():
+    """Any linear extension of the dependency DAG is a valid order for the executor."""
+    D, N = 4, 4
+    base = so.generate(D, N)
+    rng = random.Random(0)
+    for _ in range(5):
+        pending = list(base)
+        out, seen = [], set()
+        while pending:
+            ready = []
+            for o in pending:
+                if o.kind == "F":
+                    ok = o.stage == 0 or ("F", o.stage - 1, o.mb) in seen
+                else:
+                    ok = ("F", o.stage, o.mb) in seen and (
+                        o.stage == 2 * D - 1 or ("B", o.stage + 1, o.mb) in seen)
+                if ok:
+                    ready.append(o)
+            o = rng.choice(ready)
+            pending.remove(o)
+            seen.add((o.kind, o.stage, o.mb))
+            out.append(o)
+        assert so.validate(out, D, N) is None
+
+
+def test_bad_arguments():
+    for D, N in [(3, 3), (4, 6), (0, 4), (4, 2)]:
+        with pytest.raises(ValueError):
+            so.generate_timeline(D, N)
