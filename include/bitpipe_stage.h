@@ -1,0 +1,256 @@
+/*
+ * bitpipe_stage.h -- C ABI of the MI355X stage-compute library for the BitPipe schedule
+ * (arXiv 2410.19367).
+ *
+ * The unit of work that the paper's bidirectional interleaved schedule orders is the forward or
+ * the backward pass of one pipeline stage (a contiguous chunk of transformer layers) on one
+ * micro-batch (Section 3.2, Section 3.3; costs t_f and t_b of Appendix B, Eq. 1).  Training is
+ * synchronous: weight gradients of all micro-batches of an iteration are accumulated before the
+ * flush (Section 1, Section 2).  This library runs that unit of work, and a whole iteration of
+ * the V-shaped bidirectional order time-sliced on one GPU, with hand-written gfx950 kernels.
+ *
+ * One pre-LN layer, row-major activations [tokens, hidden] with token t = b*seq + s:
+ *     a   = LN(x; ln1_g, ln1_b)             qkv = a Wqkv + bqkv      (columns [q | k | v],
+ *     ctx = softmax(q k^T / sqrt(d) + mask) v                          head-major inside each)
+ *     y   = x + ctx Wo + bo
+ *     m   = LN(y; ln2_g, ln2_b)             g = GELU_tanh(m W1 + b1)
+ *     z   = y + g W2 + b2
+ * Weight matrices are row-major [in, out].  LayerNorm uses the biased variance.  The causal mask
+ * keeps keys j <= i; the padding mask keeps keys j < len_b (queries are never masked).
+ *
+ * Conventions
+ *   - Every function returns 0 (BP_OK) or a negative bp_status; bp_last_error() returns a
+ *     thread-local message for the last failure.  No exception crosses the boundary.
+ *   - "dev" pointers are HIP device pointers owned by the caller; "host" pointers are ordinary
+ *     host memory.  The library owns weights, gradient accumulators, stashes and workspaces.
+ *   - Activation tensors are [microbatch, seq, hidden] in the stage's dtype (BP_BF16: 2-byte
+ *     bfloat16; BP_F32: 4-byte float).
+ *   - Calls enqueue work on the stage's HIP stream and return without synchronising, except
+ *     where stated.  A stage object must not be used from two threads at once.
+ */
+#ifndef BITPIPE_STAGE_H
+#define BITPIPE_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bp_stage bp_stage_t;   /* opaque, library-owned */
+
+enum bp_status {
+    BP_OK = 0,
+    BP_EINVAL = -1,   /* bad argument (null pointer, index out of range, odd D, ...)      */
+    BP_ESHAPE = -2,   /* shape the kernels do not support                                  */
+    BP_ESTATE = -3,   /* call order misuse: double forward, backward without forward, ...  */
+    BP_EDEP = -4,     /* schedule order fails validation                                    */
+    BP_ENOMEM = -5,   /* device or host allocation failed                                   */
+    BP_EHIP = -6      /* a HIP runtime call failed                                          */
+};
+
+enum bp_dtype { BP_F32 = 0, BP_BF16 = 1 };
+
+/* Parameter tensors of one layer.  Shapes (H = hidden, F = mlp width):
+ * LN1_G, LN1_B, LN2_G, LN2_B, BO, B2: [H]; WQKV: [H,3H]; BQKV: [3H]; WO: [H,H];
+ * W1: [H,F]; B1: [F]; W2: [F,H]. */
+enum bp_tensor_id {
+    BP_LN1_G = 0, BP_LN1_B, BP_WQKV, BP_BQKV, BP_WO, BP_BO,
+    BP_LN2_G, BP_LN2_B, BP_W1, BP_B1, BP_W2, BP_B2, BP_N_TENSORS
+};
+
+typedef struct bp_opts {
+    int n_chunks;       /* chunks (stages) held by this object; 0 -> 1                       */
+    int mlp;            /* MLP width F; 0 -> 4*hidden (Table 3's 12*L*H^2 parameter count)   */
+    int dtype;          /* bp_dtype; storage type of activations and weight matrices          */
+    int max_inflight;   /* most (chunk, micro-batch) stashes alive at once; 0 -> 8           */
+    float ln_eps;       /* 0 -> 1e-5                                                          */
+    void* hip_stream;   /* hipStream_t to enqueue on; NULL -> the default stream             */
+} bp_opts;
+
+/* Create a stage object holding one chunk of `layers` pre-LN transformer layers in bf16 with
+ * fp32 accumulation (the paper's mixed precision, Section 4.1): the compute unit of Section 3.3.
+ * causal = 1: GPT-style mask; 0: BERT-style bidirectional attention with optional key padding.
+ * Parameters start as LN gamma = 1, everything else 0; gradients start at 0.
+ * Requirements: hidden % heads == 0, hidden % 8 == 0, head dim % 8 == 0.
+ * Errors: BP_EINVAL, BP_ESHAPE, BP_ENOMEM, BP_EHIP.  *out is set only on success. */
+int bp_stage_init(bp_stage_t** out, int layers, int hidden, int heads, int seq,
+                  int microbatch, int causal);
+
+/* As bp_stage_init with explicit options (several chunks, fp32 storage, MLP width, stream).
+ * opts may be NULL (defaults). */
+int bp_stage_init_ex(bp_stage_t** out, int layers, int hidden, int heads, int seq,
+                     int microbatch, int causal, const bp_opts* opts);
+
+/* Synchronise the stream, free everything the object owns.  NULL is accepted. */
+int bp_stage_destroy(bp_stage_t* st);
+
+/* Copy one parameter tensor from host fp32 (n elements, must equal the tensor's size) into the
+ * library's device copy, rounding weight matrices to the stage dtype (nearest even).
+ * Vectors (LN gamma/beta, biases) are kept in fp32.  Synchronous. */
+int bp_stage_set_param(bp_stage_t* st, int chunk, int layer, int tensor_id,
+                       const float* host_f32, size_t n);
+
+/* Copy one fp32 gradient accumulator to the host (n must equal the tensor's size).
+ * Synchronises the stream first.  After bp_run_schedule the two directions are already summed. */
+int bp_stage_get_grad(bp_stage_t* st, int chunk, int layer, int tensor_id,
+                      float* host_f32, size_t n);
+
+/* Zero all gradient accumulators (the flush between iterations, Section 2).  Asynchronous. */
+int bp_stage_zero_grad(bp_stage_t* st);
+
+/* BERT-style key padding: valid lengths (host int32 [microbatch], each in 1..seq) used by the
+ * forward and backward of micro-batch `mb` from now on; lens = NULL clears them (full length).
+ * BP_ESTATE on a causal stage or while `mb` has a live stash. */
+int bp_stage_set_seqlens(bp_stage_t* st, int mb, const int32_t* lens_host);
+
+/* Forward of chunk `chunk` on micro-batch `mb` (the box "F" of the paper's schedule figures):
+ * act_in (dev, [B,S,H]) -> act_out (dev, [B,S,H]); what the backward needs is stashed under
+ * (chunk, mb).  act_out may be the act_in of the next stage's forward (that hand-off is the
+ * paper's P2P message or, at the V turn, its local copy -- Section 3.2); act_in and act_out must
+ * not overlap.  BP_ESTATE: (chunk, mb) already stashed, or max_inflight stashes alive. */
+int bp_stage_forward(bp_stage_t* st, int chunk, int mb, const void* act_in, void* act_out);
+
+/* Backward of chunk `chunk` on micro-batch `mb` (the box "B"): grad_out (dev, [B,S,H], gradient
+ * w.r.t. the chunk's output) -> grad_in (dev, [B,S,H], w.r.t. its input); every parameter
+ * gradient of the chunk is accumulated in fp32 (+=) and the stash of (chunk, mb) is released.
+ * grad_in may alias grad_out.  BP_ESTATE: no stashed forward for (chunk, mb). */
+int bp_stage_backward(bp_stage_t* st, int chunk, int mb, const void* grad_out, void* grad_in);
+
+/* As bp_stage_backward, accumulating into the gradient buffer of pipeline direction `direction`
+ * (0 down, 1 up): the two replicas of a stage that Section 3.4's all-reduce synchronises. */
+int bp_stage_backward_dir(bp_stage_t* st, int chunk, int mb, const void* grad_out,
+                          void* grad_in, int direction);
+
+/* One operation of a schedule: forward or backward of global stage `stage` (= chunk index) on
+ * micro-batch `mb`, in pipeline `dir`, placed on virtual device `vdev`. */
+typedef struct bp_op {
+    int8_t kind;      /* 0 forward, 1 backward */
+    int8_t dir;       /* 0 down pipeline, 1 up pipeline */
+    int16_t vdev;     /* virtual device 0..D-1 */
+    int32_t stage;    /* 0..2D-1 */
+    int32_t mb;       /* 0..N-1 */
+} bp_op;
+
+enum bp_schedule_variant { BP_SCHED_V_CONCAT = 0 };
+
+/* Pure CPU.  Stage -> virtual device of the V-shaped map (Section 3.2, Section 3.3):
+ * down: 0..D-1 then D-1..0; up: the mirror image.  Returns -1 on bad arguments. */
+int bp_schedule_vmap(int dir, int stage, int D);
+
+/* Pure CPU.  Write the serial order of one BitPipe iteration with D virtual devices, 2D stages
+ * and N micro-batches (N a multiple of D, D even; Section 3.3 basic unit, Section 3.5
+ * concatenation) into out[0..cap); *n_out = 4*D*N ops.  The order is the list schedule under
+ * the paper's cost model (chunk forward 1, backward 2), serialised by (start time, device).
+ * BP_EINVAL for odd D, N % D != 0, cap too small or an unknown variant. */
+int bp_schedule_generate(int D, int N, int variant, bp_op* out, int cap, int* n_out);
+
+/* Pure CPU.  BP_OK iff the order holds exactly one forward and one backward per (stage, mb),
+ * every op comes after the ops it depends on, vdev matches the V map and a micro-batch keeps
+ * one direction; else BP_EDEP (bp_last_error names the first violation). */
+int bp_schedule_validate(const bp_op* order, int n_ops, int D, int N);
+
+/* Pure CPU.  Simulate `order` under the cost model (forward cost_f, backward cost_b per chunk)
+ * with each op starting as soon as its device and its inputs are free, keeping the list's
+ * per-device order.  Outputs (each may be NULL): makespan, idle[D] per device, peak_stash[D]. */
+int bp_schedule_simulate(const bp_op* order, int n_ops, int D, int N, int cost_f, int cost_b,
+                         int* makespan, int* idle, int* peak_stash);
+
+/* Run a whole iteration on one GPU (Section 3.3 / 3.5 order, all virtual devices time-sliced).
+ * The object must hold n_chunks == 2*D chunks.  order is validated first (BP_EDEP, nothing is
+ * launched); gradients are zeroed; ops run in list order, the output of stage s feeding stage
+ * s+1 (the emulated P2P / local copy); after the last stage's forward of micro-batch m the loss
+ *     L_m = 1/(N*B*S) * sum_{b,s} 0.5 * || z_m[b,s,:] - targets[m,b,s,:] ||^2
+ * and its gradient seed the backward; backward ops accumulate into their direction's gradient
+ * buffer and at the end the two are summed (the all-reduce of Section 3.4 on one device).
+ * inputs, targets: dev [N,B,S,H] in the stage dtype.  loss_out (host, may be NULL) receives
+ * sum_m L_m.  Synchronises before returning. */
+int bp_run_schedule(bp_stage_t* st, const bp_op* order, int n_ops, int D,
+                    const void* inputs_dev, const void* targets_dev, float* loss_out);
+
+/* ---- per-kernel timing (HIP events recorded on the stage's stream around every launch) ---- */
+
+enum bp_kernel_id {
+    BP_K_GEMM = 0,        /* all linear-layer GEMMs: forward, dgrad, wgrad          */
+    BP_K_ATTN_FWD,
+    BP_K_ATTN_BWD,
+    BP_K_LN_FWD,
+    BP_K_LN_BWD,
+    BP_K_GELU_FWD,
+    BP_K_GELU_BWD,
+    BP_K_COLSUM,          /* bias / LN parameter gradient column reductions         */
+    BP_K_OTHER,           /* copies, casts, loss, gradient merge                    */
+    BP_N_KERNEL_IDS
+};
+
+/* Turn event timing on (1) or off (0) and clear the counters.  While on, every launch is
+ * bracketed by two events on the stage's stream; off is the default and costs nothing. */
+int bp_prof_enable(bp_stage_t* st, int on);
+
+/* Synchronise and read the totals of one kernel class since bp_prof_enable(st, 1):
+ * milliseconds between the events, number of launches, algorithmic flops and algorithmic bytes
+ * (what the class had to compute / move by the layer definition, not what it actually did). */
+int bp_prof_get(bp_stage_t* st, int kernel_id, double* total_ms, long long* launches,
+                double* flops, double* bytes);
+
+/* ---- single operations on caller-owned device buffers (tests and kernel benchmarks) ------ */
+
+/* C = op(A) * op(B) (+ bias) (+ residual), or C += op(A) * op(B) when accumulate != 0.
+ * dtype: storage type of A, B, residual and (when accumulate == 0) C; with accumulate != 0, C is
+ * fp32.  op(A) is [M,K]: a_t == 0 -> A[m*lda + k]; a_t != 0 -> A[k*lda + m].  op(B) is [K,N]:
+ * b_t == 0 -> B[k*ldb + n]; b_t != 0 -> B[n*ldb + k].  bias: fp32 [N] or NULL.  residual: [M,N]
+ * leading dimension ldc, or NULL.  These are the three shapes of a linear layer: forward
+ * (a_t=0,b_t=0), dgrad (0,1) and wgrad (1,0, accumulate).  stream: hipStream_t or NULL. */
+int bp_op_gemm(int dtype, int a_t, int b_t, int M, int N, int K,
+               const void* A, int lda, const void* B, int ldb, void* C, int ldc,
+               const float* bias, const void* residual, int accumulate, void* stream);
+
+/* out = LN(x) over rows of [T,H]; writes mean and rstd (fp32 [T]). */
+int bp_op_layernorm_fwd(int dtype, int T, int H, const void* x, const float* gamma,
+                        const float* beta, float eps, void* out, float* mean, float* rstd,
+                        void* stream);
+
+/* dx = residual_grad + LNbwd(dout) (residual_grad may be NULL); dgamma, dbeta (fp32 [H]) are
+ * accumulated (+=).  workspace: dev fp32, at least bp_op_colsum_workspace(T, H) * 2 floats. */
+int bp_op_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* x,
+                        const float* mean, const float* rstd, const float* gamma,
+                        const void* residual_grad, void* dx, float* dgamma, float* dbeta,
+                        float* workspace, void* stream);
+
+/* g = GELU_tanh(u + bias) over [T,F]. */
+int bp_op_bias_gelu_fwd(int dtype, int T, int F, const void* u, const float* bias, void* g,
+                        void* stream);
+
+/* du = dg * GELU'(u + bias); dbias (fp32 [F]) += column sums of du.  workspace as above. */
+int bp_op_bias_gelu_bwd(int dtype, int T, int F, const void* dg, const void* u,
+                        const float* bias, void* du, float* dbias, float* workspace,
+                        void* stream);
+
+/* Number of fp32 elements of workspace one column reduction over [T,N] needs. */
+size_t bp_op_colsum_workspace(int T, int N);
+
+/* Fused attention forward on a packed qkv tensor [B*S, 3H] (columns [q|k|v], head-major):
+ * ctx [B*S, H], lse fp32 [B, heads, S] (log-sum-exp of the scaled, masked scores).
+ * lens: dev int32 [B] or NULL. */
+int bp_op_attention_fwd(int dtype, int B, int S, int heads, int head_dim, int causal,
+                        const int32_t* lens_dev, const void* qkv, void* ctx, float* lse,
+                        void* stream);
+
+/* Fused attention backward: dqkv [B*S, 3H] from dctx, the forward's qkv, ctx and lse.
+ * delta: dev fp32 workspace [B, heads, S]. */
+int bp_op_attention_bwd(int dtype, int B, int S, int heads, int head_dim, int causal,
+                        const int32_t* lens_dev, const void* qkv, const void* ctx,
+                        const float* lse, const void* dctx, void* dqkv, float* delta,
+                        void* stream);
+
+/* Message of the last failure on this thread ("" if none). */
+const char* bp_last_error(void);
+
+/* Library version string. */
+const char* bp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITPIPE_STAGE_H */

@@ -1,0 +1,18 @@
+// Kernel selection: which implementation serves a given GEMM / attention shape.
+#include "bp_kernels.h"
+
+namespace bp {
+
+hipError_t launch_gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
+    return launch_gemm_generic(dtype, g, stream);
+}
+
+hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t stream) {
+    return launch_attn_fwd_generic(dtype, a, stream);
+}
+
+hipError_t launch_attn_bwd(int dtype, const AttnArgs& a, hipStream_t stream) {
+    return launch_attn_bwd_generic(dtype, a, stream);
+}
+
+}  // namespace bp

@@ -1,0 +1,85 @@
+// Internal launch interface between the host-side stage logic and the gfx950 kernels.
+// Every function enqueues on `stream` and returns the launch status; none synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace bp {
+
+enum DType { F32 = 0, BF16 = 1 };
+
+inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
+
+// C = op(A) op(B) (+bias) (+residual)  or  C(fp32) += op(A) op(B).
+//   op(A)[m,k] = a_t ? A[k*lda + m] : A[m*lda + k]
+//   op(B)[k,n] = b_t ? B[n*ldb + k] : B[k*ldb + n]
+struct GemmArgs {
+    const void* A; const void* B; void* C;
+    const float* bias;       // [N] or null
+    const void* residual;    // [M,N] ld = ldc, storage dtype, or null
+    int M, N, K;
+    int lda, ldb, ldc;
+    int a_t, b_t;
+    int accumulate;          // 1: C is fp32 and receives +=
+};
+
+// picks the MFMA kernel when the shape allows it, else the generic one
+hipError_t launch_gemm(int dtype, const GemmArgs& g, hipStream_t stream);
+hipError_t launch_gemm_generic(int dtype, const GemmArgs& g, hipStream_t stream);
+
+// rows kept per partial of a column reduction
+constexpr int kColsumRows = 32;
+inline size_t colsum_chunks(int T) { return (size_t)((T + kColsumRows - 1) / kColsumRows); }
+
+hipError_t launch_ln_fwd(int dtype, int T, int H, const void* x, const float* gamma,
+                         const float* beta, float eps, void* out, float* mean, float* rstd,
+                         void* xcopy, hipStream_t stream);
+
+// dx = res + LNbwd(dout) row by row (res may be null)
+hipError_t launch_ln_bwd_rows(int dtype, int T, int H, const void* dout, const void* x,
+                              const float* mean, const float* rstd, const float* gamma,
+                              const void* res, void* dx, hipStream_t stream);
+
+// Column reductions over [T,N] into fp32 accumulators (+=):
+//   out_a[c]  += sum_t A[t,c]
+//   out_ax[c] += sum_t A[t,c] * (X[t,c]-mean[t])*rstd[t]     (only when X != null)
+// ws: colsum_chunks(T) * N * (X ? 2 : 1) floats.
+hipError_t launch_colsum(int dtype, int T, int N, const void* A, const void* X,
+                         const float* mean, const float* rstd, float* out_a, float* out_ax,
+                         float* ws, hipStream_t stream);
+
+hipError_t launch_gelu_fwd(int dtype, int T, int F, const void* u, const float* bias, void* g,
+                           hipStream_t stream);
+
+// du = dg * gelu'(u + bias); dbias += colsum(du).  ws: colsum_chunks(T) * F floats.
+hipError_t launch_gelu_bwd(int dtype, int T, int F, const void* dg, const void* u,
+                           const float* bias, void* du, float* dbias, float* ws,
+                           hipStream_t stream);
+
+struct AttnArgs {
+    int B, S, heads, d, causal;
+    const int32_t* lens;     // dev [B] or null
+    const void* qkv;         // [B*S, 3*heads*d]
+    void* ctx;               // fwd: out; bwd: in  [B*S, heads*d]
+    float* lse;              // [B, heads, S]
+    const void* dctx;        // bwd
+    void* dqkv;              // bwd out
+    float* delta;            // bwd workspace [B, heads, S]
+};
+hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t stream);
+hipError_t launch_attn_bwd(int dtype, const AttnArgs& a, hipStream_t stream);
+hipError_t launch_attn_fwd_generic(int dtype, const AttnArgs& a, hipStream_t stream);
+hipError_t launch_attn_bwd_generic(int dtype, const AttnArgs& a, hipStream_t stream);
+
+// grad = (z - target) * scale in the storage dtype; loss_out[0] = 0.5 * scale * sum (z-target)^2.
+// ws: at least 1024 floats.
+hipError_t launch_loss(int dtype, size_t n, const void* z, const void* target, float scale,
+                       void* grad, float* loss_out, float* ws, hipStream_t stream);
+
+hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t stream);
+hipError_t launch_add_f32(float* dst, const float* src, size_t n, hipStream_t stream);   // dst += src
+// host fp32 staging (already on device as fp32) -> storage dtype
+hipError_t launch_cast_from_f32(int dtype, const float* src, void* dst, size_t n, hipStream_t stream);
+
+}  // namespace bp

@@ -1,0 +1,313 @@
+// The BitPipe order on the host: V-shaped stage->device map, list-scheduled generation of one
+// iteration, validation, a cost-model replay, and the executor that runs an iteration with all
+// virtual devices time-sliced on one GPU.
+#include <algorithm>
+#include <climits>
+#include <vector>
+
+#include "bp_host.h"
+
+namespace bp {
+
+// Section 3.2 / 3.3: the down pipeline places stages 0..D-1 on devices 0..D-1 and stages
+// D..2D-1 on devices D-1..0; the up pipeline is its mirror image.
+int schedule_vmap(int dir, int stage, int D) {
+    if (D <= 0 || stage < 0 || stage >= 2 * D || (dir != 0 && dir != 1)) return -1;
+    const int down = stage < D ? stage : 2 * D - 1 - stage;
+    return dir == 0 ? down : D - 1 - down;
+}
+
+// Within each group of D consecutive micro-batches the first half travels down, the second up
+// (each pipeline schedules N/2 micro-batches, Section 3.3).
+static inline int direction_of(int mb, int D) { return (mb % D) < D / 2 ? 0 : 1; }
+
+namespace {
+
+struct Timed {
+    int start;
+    bp_op op;
+};
+
+// State of the list scheduler: finish times per (stage, mb), busy-until per device.
+struct ListScheduler {
+    int D, N, n_stage, cost_f, cost_b;
+    std::vector<int> f_done, b_done;        // finish time or INT_MAX while not finished
+    std::vector<char> f_started, b_started;
+    std::vector<int> busy_until, f_count;
+    std::vector<std::vector<int>> b_ends;   // per device: finish times of started backwards
+    std::vector<int> admitted;
+    std::vector<Timed> out;
+
+    ListScheduler(int D_, int N_, int cf, int cb)
+        : D(D_), N(N_), n_stage(2 * D_), cost_f(cf), cost_b(cb),
+          f_done((size_t)2 * D_ * N_, INT_MAX), b_done((size_t)2 * D_ * N_, INT_MAX),
+          f_started((size_t)2 * D_ * N_, 0), b_started((size_t)2 * D_ * N_, 0),
+          busy_until(D_, 0), f_count(D_, 0), b_ends(D_) {}
+
+    size_t at(int s, int mb) const { return (size_t)mb * n_stage + s; }
+
+    int held(int dev, int t) const {   // stashes alive on dev: forwards started - backwards finished
+        int done = 0;
+        for (int e : b_ends[dev]) done += e <= t;
+        return f_count[dev] - done;
+    }
+    int in_flight(int t) const {       // admitted micro-batches whose stage-0 backward is not finished
+        int n = 0;
+        for (int mb : admitted) n += b_done[at(0, mb)] > t;
+        return n;
+    }
+
+    // Pick what device `dev` starts at time t, or nothing.  Backwards first (lowest micro-batch,
+    // then lowest stage); else the forward of the deepest stage (then lowest micro-batch).
+    bool pick(int dev, int t, bp_op* chosen) const {
+        const int cap = 2 * D, window = D + D / 2;
+        bool have_b = false, have_f = false;
+        int b_mb = 0, b_s = 0, f_mb = 0, f_s = 0;
+        const bool room = held(dev, t) < cap;
+        const bool may_admit = in_flight(t) < window;
+        for (int mb = 0; mb < N; ++mb) {
+            const int dir = direction_of(mb, D);
+            for (int s = 0; s < n_stage; ++s) {
+                if (schedule_vmap(dir, s, D) != dev) continue;
+                const size_t k = at(s, mb);
+                if (!b_started[k] && f_done[k] <= t &&
+                    (s == n_stage - 1 || b_done[at(s + 1, mb)] <= t)) {
+                    if (!have_b || mb < b_mb || (mb == b_mb && s < b_s)) { have_b = true; b_mb = mb; b_s = s; }
+                }
+                if (!f_started[k] && room) {
+                    const bool ready = s == 0 ? may_admit : f_done[at(s - 1, mb)] <= t;
+                    if (ready && (!have_f || s > f_s || (s == f_s && mb < f_mb))) { have_f = true; f_mb = mb; f_s = s; }
+                }
+            }
+        }
+        if (have_b) {
+            *chosen = bp_op{1, (int8_t)direction_of(b_mb, D), (int16_t)dev, b_s, b_mb};
+            return true;
+        }
+        if (have_f) {
+            *chosen = bp_op{0, (int8_t)direction_of(f_mb, D), (int16_t)dev, f_s, f_mb};
+            return true;
+        }
+        return false;
+    }
+
+    bool run() {
+        const size_t total = (size_t)2 * n_stage * N;
+        const long horizon = (long)(cost_f + cost_b) * (long)total + 1;
+        for (int t = 0; out.size() < total; ++t) {
+            if (t > horizon) return false;
+            for (int dev = 0; dev < D; ++dev) {
+                if (busy_until[dev] > t) continue;
+                bp_op op;
+                if (!pick(dev, t, &op)) continue;
+                const size_t k = at(op.stage, op.mb);
+                if (op.kind == 0) {
+                    if (op.stage == 0) admitted.push_back(op.mb);
+                    f_started[k] = 1;
+                    f_done[k] = t + cost_f;
+                    f_count[dev] += 1;
+                    busy_until[dev] = t + cost_f;
+                } else {
+                    b_started[k] = 1;
+                    b_done[k] = t + cost_b;
+                    b_ends[dev].push_back(t + cost_b);
+                    busy_until[dev] = t + cost_b;
+                }
+                out.push_back({t, op});
+            }
+        }
+        return true;
+    }
+};
+
+}  // namespace
+
+static int schedule_generate(int D, int N, int variant, bp_op* out, int cap, int* n_out) {
+    if (variant != BP_SCHED_V_CONCAT) return fail(BP_EINVAL, "unknown schedule variant %d", variant);
+    if (D < 2 || D % 2) return fail(BP_EINVAL, "D = %d must be even and >= 2", D);
+    if (N < D || N % D) return fail(BP_EINVAL, "N = %d must be a positive multiple of D = %d", N, D);
+    if (D > 1024 || N > 65536) return fail(BP_EINVAL, "D or N too large");
+    const long total = 4L * D * N;
+    if (!out || !n_out || cap < total) return fail(BP_EINVAL, "output array too small (need %ld ops)", total);
+    ListScheduler ls(D, N, 1, 2);
+    if (!ls.run()) return fail(BP_EINVAL, "list scheduler made no progress for D = %d, N = %d", D, N);
+    // one GPU runs the devices' ops one after another: order by (start time, device)
+    std::stable_sort(ls.out.begin(), ls.out.end(), [](const Timed& a, const Timed& b) {
+        return a.start != b.start ? a.start < b.start : a.op.vdev < b.op.vdev;
+    });
+    for (long i = 0; i < total; ++i) out[i] = ls.out[i].op;
+    *n_out = (int)total;
+    return BP_OK;
+}
+
+int schedule_validate(const bp_op* order, int n_ops, int D, int N) {
+    if (!order) return fail(BP_EINVAL, "order is null");
+    if (D < 2 || D % 2) return fail(BP_EINVAL, "D = %d must be even and >= 2", D);
+    if (N < 1) return fail(BP_EINVAL, "N = %d must be positive", N);
+    const int n_stage = 2 * D;
+    if ((long)n_ops != 2L * n_stage * N)
+        return fail(BP_EDEP, "order has %d ops, an iteration needs %ld", n_ops, 2L * n_stage * N);
+    std::vector<char> f_seen((size_t)n_stage * N, 0), b_seen((size_t)n_stage * N, 0);
+    std::vector<int> mb_dir(N, -1);
+    for (int i = 0; i < n_ops; ++i) {
+        const bp_op& o = order[i];
+        if ((o.kind != 0 && o.kind != 1) || (o.dir != 0 && o.dir != 1))
+            return fail(BP_EDEP, "op %d: bad kind or direction", i);
+        if (o.stage < 0 || o.stage >= n_stage || o.mb < 0 || o.mb >= N)
+            return fail(BP_EDEP, "op %d: stage %d or micro-batch %d out of range", i, o.stage, o.mb);
+        if (o.vdev != schedule_vmap(o.dir, o.stage, D))
+            return fail(BP_EDEP, "op %d: device %d does not match the V map", i, o.vdev);
+        if (mb_dir[o.mb] < 0) mb_dir[o.mb] = o.dir;
+        else if (mb_dir[o.mb] != o.dir) return fail(BP_EDEP, "op %d: micro-batch %d changes direction", i, o.mb);
+        const size_t k = (size_t)o.mb * n_stage + o.stage;
+        if (o.kind == 0) {
+            if (f_seen[k]) return fail(BP_EDEP, "op %d: duplicate forward (stage %d, mb %d)", i, o.stage, o.mb);
+            if (o.stage > 0 && !f_seen[k - 1])
+                return fail(BP_EDEP, "op %d: forward (stage %d, mb %d) before its producer", i, o.stage, o.mb);
+            f_seen[k] = 1;
+        } else {
+            if (b_seen[k]) return fail(BP_EDEP, "op %d: duplicate backward (stage %d, mb %d)", i, o.stage, o.mb);
+            if (!f_seen[k]) return fail(BP_EDEP, "op %d: backward (stage %d, mb %d) before its forward", i, o.stage, o.mb);
+            if (o.stage < n_stage - 1 && !b_seen[k + 1])
+                return fail(BP_EDEP, "op %d: backward (stage %d, mb %d) before its upstream backward", i, o.stage, o.mb);
+            b_seen[k] = 1;
+        }
+    }
+    return BP_OK;   // n_ops == 2 * n_stage * N and no duplicates => every op is present
+}
+
+static int schedule_simulate(const bp_op* order, int n_ops, int D, int N, int cost_f, int cost_b,
+                             int* makespan, int* idle, int* peak_stash) {
+    int rc = schedule_validate(order, n_ops, D, N);
+    if (rc) return rc;
+    if (cost_f <= 0 || cost_b <= 0) return fail(BP_EINVAL, "costs must be positive");
+    const int n_stage = 2 * D;
+    std::vector<int> f_done((size_t)n_stage * N, 0), b_done((size_t)n_stage * N, 0), busy(D, 0), work(D, 0);
+    std::vector<std::vector<std::pair<int, int>>> events(D);   // (time, +1 at F start / -1 at B end)
+    int ms = 0;
+    for (int i = 0; i < n_ops; ++i) {
+        const bp_op& o = order[i];
+        const size_t k = (size_t)o.mb * n_stage + o.stage;
+        int ready;
+        if (o.kind == 0) ready = o.stage == 0 ? 0 : f_done[k - 1];
+        else ready = std::max(f_done[k], o.stage == n_stage - 1 ? 0 : b_done[k + 1]);
+        const int start = std::max(ready, busy[o.vdev]);
+        const int cost = o.kind == 0 ? cost_f : cost_b;
+        busy[o.vdev] = start + cost;
+        work[o.vdev] += cost;
+        if (o.kind == 0) { f_done[k] = start + cost; events[o.vdev].push_back({start, 1}); }
+        else { b_done[k] = start + cost; events[o.vdev].push_back({start + cost, -1}); }
+        ms = std::max(ms, start + cost);
+    }
+    if (makespan) *makespan = ms;
+    for (int dev = 0; dev < D; ++dev) {
+        if (idle) idle[dev] = ms - work[dev];
+        if (peak_stash) {
+            auto& ev = events[dev];
+            std::sort(ev.begin(), ev.end());   // at equal times releases (-1) sort before acquisitions
+            int cur = 0, peak = 0;
+            for (auto& e : ev) { cur += e.second; peak = std::max(peak, cur); }
+            peak_stash[dev] = peak;
+        }
+    }
+    return BP_OK;
+}
+
+// ------------------------------------------------------------------ executor
+
+int Stage::live_slots() const {
+    int n = 0;
+    for (auto& s : slots) n += s.live;
+    return n;
+}
+
+int Stage::run_schedule(const bp_op* order, int n_ops, int D, const void* inputs, const void* targets,
+                        float* loss_out) {
+    if (!order || !inputs || !targets) return fail(BP_EINVAL, "null argument");
+    if (D < 2 || D % 2) return fail(BP_EINVAL, "D = %d must be even and >= 2", D);
+    if (n_chunks != 2 * D) return fail(BP_EINVAL, "stage object holds %d chunks, the order needs 2*D = %d", n_chunks, 2 * D);
+    if (n_ops <= 0 || n_ops % (4 * D)) return fail(BP_EDEP, "order has %d ops, not a multiple of 4*D", n_ops);
+    const int N = n_ops / (4 * D);
+    int rc = schedule_validate(order, n_ops, D, N);
+    if (rc) return rc;
+    if (live_slots()) return fail(BP_ESTATE, "stashes are live at the start of an iteration");
+
+    const size_t TH = (size_t)T * H, THb = TH * esz;
+    if (sched_n < N) {
+        hipStreamSynchronize(stream);
+        hipFree(sched_act); hipFree(sched_grad); hipFree(sched_loss);
+        sched_act = sched_grad = nullptr; sched_loss = nullptr; sched_n = 0;
+        if (hipMalloc(&sched_act, (size_t)N * 2 * THb) != hipSuccess ||
+            hipMalloc(&sched_grad, (size_t)N * THb) != hipSuccess ||
+            hipMalloc((void**)&sched_loss, (size_t)N * sizeof(float)) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(BP_ENOMEM, "allocating the iteration's hand-off buffers failed");
+        }
+        sched_n = N;
+    }
+    // an order may keep every (stage, mb) stashed at once; slots get memory only when used
+    if ((int)slots.size() < 2 * D * N) slots.resize((size_t)2 * D * N);
+
+    if ((rc = zero_grad())) return rc;
+    const int last = 2 * D - 1;
+    const float scale = 1.f / ((float)N * (float)B * (float)S);
+    for (int i = 0; i < n_ops; ++i) {
+        const bp_op& o = order[i];
+        // stage s writes hand-off buffer s%2 of its micro-batch and reads the other one: the
+        // P2P message between devices, or the local copy at the V turn
+        char* mb_act = (char*)sched_act + (size_t)o.mb * 2 * THb;
+        char* mb_grad = (char*)sched_grad + (size_t)o.mb * THb;
+        if (o.kind == 0) {
+            const void* in = o.stage == 0 ? (const char*)inputs + (size_t)o.mb * THb
+                                          : mb_act + (size_t)((o.stage - 1) & 1) * THb;
+            void* out = mb_act + (size_t)(o.stage & 1) * THb;
+            if ((rc = forward(o.stage, o.mb, in, out))) return rc;
+            if (o.stage == last) {
+                struct Guard { Stage* s; Guard(Stage* st) : s(st) { s->prof.begin(s, BP_K_OTHER, 0, 0); } ~Guard() { s->prof.end(s); } } g(this);
+                hipError_t e = launch_loss(dtype, TH, out, (const char*)targets + (size_t)o.mb * THb, scale,
+                                           mb_grad, sched_loss + o.mb, ws_colsum, stream);
+                if (e != hipSuccess) return fail(BP_EHIP, "loss kernel: %s", hipGetErrorString(e));
+            }
+        } else {
+            if ((rc = backward(o.stage, o.mb, mb_grad, mb_grad, o.dir))) return rc;
+        }
+    }
+    if ((rc = merge_directions())) return rc;
+    std::vector<float> host_loss(N);
+    hipError_t e = hipMemcpyAsync(host_loss.data(), sched_loss, N * sizeof(float), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(BP_EHIP, "end of iteration: %s", hipGetErrorString(e));
+    if (loss_out) {
+        double s = 0.0;
+        for (int m = 0; m < N; ++m) s += host_loss[m];
+        *loss_out = (float)s;
+    }
+    return BP_OK;
+}
+
+}  // namespace bp
+
+extern "C" {
+
+int bp_schedule_vmap(int dir, int stage, int D) { return bp::schedule_vmap(dir, stage, D); }
+
+int bp_schedule_generate(int D, int N, int variant, bp_op* out, int cap, int* n_out) {
+    return bp::schedule_generate(D, N, variant, out, cap, n_out);
+}
+
+int bp_schedule_validate(const bp_op* order, int n_ops, int D, int N) {
+    return bp::schedule_validate(order, n_ops, D, N);
+}
+
+int bp_schedule_simulate(const bp_op* order, int n_ops, int D, int N, int cost_f, int cost_b,
+                         int* makespan, int* idle, int* peak_stash) {
+    return bp::schedule_simulate(order, n_ops, D, N, cost_f, cost_b, makespan, idle, peak_stash);
+}
+
+int bp_run_schedule(bp_stage_t* st, const bp_op* order, int n_ops, int D, const void* inputs,
+                    const void* targets, float* loss_out) {
+    if (!st) return bp::fail(BP_EINVAL, "stage handle is null");
+    return ((bp::Stage*)st)->run_schedule(order, n_ops, D, inputs, targets, loss_out);
+}
+
+}  // extern "C"

@@ -1,0 +1,562 @@
+// Host side of the stage library: the stage object (weights, fp32 gradient accumulators per
+// pipeline direction, activation stashes keyed by (chunk, micro-batch), backward workspaces),
+// the forward / backward kernel sequences of a chunk, and the C ABI around them.
+#include "bp_host.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace bp {
+
+static thread_local std::string g_last_error;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_last_error = buf;
+    return code;
+}
+
+const char* last_error() { return g_last_error.c_str(); }
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ------------------------------------------------------------------ shapes
+
+size_t Stage::tensor_elems(int id) const {
+    const size_t h = H, f = F;
+    switch (id) {
+        case BP_WQKV: return h * 3 * h;
+        case BP_BQKV: return 3 * h;
+        case BP_WO: return h * h;
+        case BP_W1: return h * f;
+        case BP_B1: return f;
+        case BP_W2: return f * h;
+        default: return h;   // LN vectors, bo, b2
+    }
+}
+
+bool Stage::tensor_is_matrix(int id) { return id == BP_WQKV || id == BP_WO || id == BP_W1 || id == BP_W2; }
+
+// ------------------------------------------------------------------ profiling
+
+void Prof::begin(Stage* st, int kid, double flops, double bytes) {
+    if (!on) return;
+    hipEvent_t a, b;
+    if (free_events.size() >= 2) {
+        a = free_events.back(); free_events.pop_back();
+        b = free_events.back(); free_events.pop_back();
+    } else {
+        hipEventCreate(&a);
+        hipEventCreate(&b);
+    }
+    hipEventRecord(a, st->stream);
+    pending.push_back({kid, a, b});
+    flops_total[kid] += flops;
+    bytes_total[kid] += bytes;
+    launches[kid] += 1;
+}
+
+void Prof::end(Stage* st) {
+    if (!on) return;
+    hipEventRecord(pending.back().stop, st->stream);
+}
+
+void Prof::collect() {
+    for (auto& p : pending) {
+        float ms = 0.f;
+        hipEventSynchronize(p.stop);
+        hipEventElapsedTime(&ms, p.start, p.stop);
+        ms_total[p.kid] += ms;
+        free_events.push_back(p.start);
+        free_events.push_back(p.stop);
+    }
+    pending.clear();
+}
+
+void Prof::reset() {
+    collect();
+    for (int i = 0; i < BP_N_KERNEL_IDS; ++i) {
+        ms_total[i] = 0; flops_total[i] = 0; bytes_total[i] = 0; launches[i] = 0;
+    }
+}
+
+Prof::~Prof() {
+    collect();
+    for (auto e : free_events) hipEventDestroy(e);
+}
+
+struct Scoped {
+    Stage* st;
+    Scoped(Stage* s, int kid, double flops, double bytes) : st(s) { st->prof.begin(st, kid, flops, bytes); }
+    ~Scoped() { st->prof.end(st); }
+};
+
+// ------------------------------------------------------------------ construction
+
+static int dev_alloc(void** p, size_t bytes) {
+    hipError_t e = hipMalloc(p, bytes ? bytes : 256);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(BP_ENOMEM, "hipMalloc(%zu bytes) failed: %s", bytes, hipGetErrorString(e));
+    }
+    return BP_OK;
+}
+
+int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int microbatch,
+                  int causal, const bp_opts* o) {
+    if (!out) return fail(BP_EINVAL, "out is null");
+    if (layers <= 0 || hidden <= 0 || heads <= 0 || seq <= 0 || microbatch <= 0)
+        return fail(BP_EINVAL, "layers, hidden, heads, seq, microbatch must be positive");
+    if (hidden % heads) return fail(BP_ESHAPE, "hidden %d is not a multiple of heads %d", hidden, heads);
+    const int d = hidden / heads;
+    if (hidden % 8 || d % 8) return fail(BP_ESHAPE, "hidden and head dim must be multiples of 8");
+    if (hidden > 8192) return fail(BP_ESHAPE, "hidden %d exceeds 8192", hidden);
+    bp_opts opt;
+    memset(&opt, 0, sizeof opt);
+    opt.dtype = BP_BF16;
+    if (o) opt = *o;
+    if (opt.dtype != BP_F32 && opt.dtype != BP_BF16) return fail(BP_EINVAL, "unknown dtype %d", opt.dtype);
+    if (opt.n_chunks < 0 || opt.mlp < 0 || opt.max_inflight < 0 || opt.ln_eps < 0)
+        return fail(BP_EINVAL, "negative option");
+    if (opt.mlp % 8) return fail(BP_ESHAPE, "mlp width must be a multiple of 8");
+    if ((size_t)seq * sizeof(float) * 2 > 56000)
+        return fail(BP_ESHAPE, "seq %d too long for the attention kernels", seq);
+
+    Stage* st = new (std::nothrow) Stage();
+    if (!st) return fail(BP_ENOMEM, "host allocation failed");
+    st->L = layers; st->H = hidden; st->heads = heads; st->d = d; st->S = seq; st->B = microbatch;
+    st->T = microbatch * seq;
+    st->causal = causal != 0;
+    st->n_chunks = opt.n_chunks ? opt.n_chunks : 1;
+    st->F = opt.mlp ? opt.mlp : 4 * hidden;
+    st->dtype = opt.dtype;
+    st->max_inflight = opt.max_inflight ? opt.max_inflight : 8;
+    st->eps = opt.ln_eps > 0 ? opt.ln_eps : 1e-5f;
+    st->stream = (hipStream_t)opt.hip_stream;
+    st->esz = dtype_size(st->dtype);
+
+    // parameter and gradient layout: one blob each, tensors 256-byte aligned
+    size_t poff = 0, goff = 0;
+    for (int t = 0; t < BP_N_TENSORS; ++t) {
+        st->p_off[t] = poff;
+        st->g_off[t] = goff;
+        const size_t n = st->tensor_elems(t);
+        poff += align_up(n * (tensor_is_matrix(t) ? st->esz : sizeof(float)), 256);
+        goff += align_up(n * sizeof(float), 256);
+    }
+    st->p_layer_bytes = poff;
+    st->g_layer_bytes = goff;
+    const size_t n_layers = (size_t)st->n_chunks * st->L;
+    int rc;
+    if ((rc = dev_alloc(&st->params, n_layers * poff))) { delete st; return rc; }
+    for (int dir = 0; dir < 2; ++dir)
+        if ((rc = dev_alloc((void**)&st->grads[dir], n_layers * goff))) { delete st; return rc; }
+
+    // stash layout of one layer
+    const size_t TH = (size_t)st->T * st->H * st->esz, TF = (size_t)st->T * st->F * st->esz;
+    size_t so = 0;
+    auto take = [&](size_t bytes) { size_t o = so; so += align_up(bytes, 256); return o; };
+    st->s_x = take(TH); st->s_a = take(TH); st->s_qkv = take(3 * TH); st->s_ctx = take(TH);
+    st->s_y = take(TH); st->s_m = take(TH); st->s_u = take(TF); st->s_g = take(TF);
+    st->s_mean1 = take(st->T * sizeof(float)); st->s_rstd1 = take(st->T * sizeof(float));
+    st->s_mean2 = take(st->T * sizeof(float)); st->s_rstd2 = take(st->T * sizeof(float));
+    st->s_lse = take((size_t)st->B * st->heads * st->S * sizeof(float));
+    st->s_layer_bytes = so;
+    st->slots.resize(st->max_inflight);
+
+    // backward workspaces
+    const size_t big = std::max((size_t)st->F, (size_t)3 * st->H);
+    if ((rc = dev_alloc(&st->ws_big1, (size_t)st->T * big * st->esz)) ||
+        (rc = dev_alloc(&st->ws_big2, (size_t)st->T * 3 * st->H * st->esz)) ||
+        (rc = dev_alloc(&st->ws_h1, TH)) || (rc = dev_alloc(&st->ws_h2, TH)) ||
+        (rc = dev_alloc(&st->ws_h3, TH)) ||
+        (rc = dev_alloc((void**)&st->ws_delta, (size_t)st->B * st->heads * st->S * sizeof(float))) ||
+        (rc = dev_alloc((void**)&st->ws_colsum,
+                        std::max<size_t>(2 * colsum_chunks(st->T) * big, 1024) * sizeof(float)))) {
+        delete st;
+        return rc;
+    }
+
+    // initial values: zeros, LN gamma = 1
+    hipError_t e = hipMemsetAsync(st->params, 0, n_layers * poff, st->stream);
+    if (e == hipSuccess) e = launch_fill_f32(st->grads[0], n_layers * goff / 4, 0.f, st->stream);
+    if (e == hipSuccess) e = launch_fill_f32(st->grads[1], n_layers * goff / 4, 0.f, st->stream);
+    for (int c = 0; c < st->n_chunks && e == hipSuccess; ++c)
+        for (int l = 0; l < st->L && e == hipSuccess; ++l) {
+            e = launch_fill_f32((float*)st->param(c, l, BP_LN1_G), st->H, 1.f, st->stream);
+            if (e == hipSuccess) e = launch_fill_f32((float*)st->param(c, l, BP_LN2_G), st->H, 1.f, st->stream);
+        }
+    if (e == hipSuccess) e = hipStreamSynchronize(st->stream);
+    if (e != hipSuccess) {
+        delete st;
+        return fail(BP_EHIP, "initialisation failed: %s", hipGetErrorString(e));
+    }
+    *out = st;
+    return BP_OK;
+}
+
+Stage::~Stage() {
+    if (stream_valid()) hipStreamSynchronize(stream);
+    hipFree(params);
+    hipFree(grads[0]);
+    hipFree(grads[1]);
+    for (auto& s : slots) hipFree(s.buf);
+    hipFree(ws_big1); hipFree(ws_big2); hipFree(ws_h1); hipFree(ws_h2); hipFree(ws_h3);
+    hipFree(ws_delta); hipFree(ws_colsum);
+    for (auto& kv : lens) hipFree(kv.second);
+    hipFree(sched_act); hipFree(sched_grad); hipFree(sched_loss);
+}
+
+void* Stage::param(int chunk, int layer, int id) const {
+    return (char*)params + ((size_t)chunk * L + layer) * p_layer_bytes + p_off[id];
+}
+float* Stage::grad(int dir, int chunk, int layer, int id) const {
+    return (float*)((char*)grads[dir] + ((size_t)chunk * L + layer) * g_layer_bytes + g_off[id]);
+}
+
+// ------------------------------------------------------------------ parameters and gradients
+
+int Stage::check_tensor(int chunk, int layer, int id, size_t n) const {
+    if (chunk < 0 || chunk >= n_chunks) return fail(BP_EINVAL, "chunk %d out of range [0,%d)", chunk, n_chunks);
+    if (layer < 0 || layer >= L) return fail(BP_EINVAL, "layer %d out of range [0,%d)", layer, L);
+    if (id < 0 || id >= BP_N_TENSORS) return fail(BP_EINVAL, "tensor id %d out of range", id);
+    if (n != tensor_elems(id))
+        return fail(BP_ESHAPE, "tensor %d has %zu elements, got %zu", id, tensor_elems(id), n);
+    return BP_OK;
+}
+
+int Stage::set_param(int chunk, int layer, int id, const float* host, size_t n) {
+    int rc = check_tensor(chunk, layer, id, n);
+    if (rc) return rc;
+    if (!host) return fail(BP_EINVAL, "host pointer is null");
+    void* dst = param(chunk, layer, id);
+    hipError_t e;
+    if (!tensor_is_matrix(id) || dtype == BP_F32) {
+        e = hipMemcpyAsync(dst, host, n * sizeof(float), hipMemcpyHostToDevice, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    } else {
+        float* tmp = nullptr;
+        if ((rc = dev_alloc((void**)&tmp, n * sizeof(float)))) return rc;
+        e = hipMemcpyAsync(tmp, host, n * sizeof(float), hipMemcpyHostToDevice, stream);
+        if (e == hipSuccess) e = launch_cast_from_f32(dtype, tmp, dst, n, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        hipFree(tmp);
+    }
+    if (e != hipSuccess) return fail(BP_EHIP, "set_param: %s", hipGetErrorString(e));
+    return BP_OK;
+}
+
+int Stage::get_grad(int chunk, int layer, int id, float* host, size_t n) {
+    int rc = check_tensor(chunk, layer, id, n);
+    if (rc) return rc;
+    if (!host) return fail(BP_EINVAL, "host pointer is null");
+    hipError_t e = hipMemcpyAsync(host, grad(0, chunk, layer, id), n * sizeof(float),
+                                  hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(BP_EHIP, "get_grad: %s", hipGetErrorString(e));
+    return BP_OK;
+}
+
+int Stage::zero_grad() {
+    const size_t n = (size_t)n_chunks * L * g_layer_bytes / sizeof(float);
+    Scoped sc(this, BP_K_OTHER, 0, 0);
+    hipError_t e = launch_fill_f32(grads[0], n, 0.f, stream);
+    if (e == hipSuccess) e = launch_fill_f32(grads[1], n, 0.f, stream);
+    if (e != hipSuccess) return fail(BP_EHIP, "zero_grad: %s", hipGetErrorString(e));
+    return BP_OK;
+}
+
+int Stage::merge_directions() {
+    const size_t n = (size_t)n_chunks * L * g_layer_bytes / sizeof(float);
+    Scoped sc(this, BP_K_OTHER, 0, 0);
+    hipError_t e = launch_add_f32(grads[0], grads[1], n, stream);
+    if (e == hipSuccess) e = launch_fill_f32(grads[1], n, 0.f, stream);
+    if (e != hipSuccess) return fail(BP_EHIP, "merge_directions: %s", hipGetErrorString(e));
+    return BP_OK;
+}
+
+int Stage::set_seqlens(int mb, const int32_t* host) {
+    if (mb < 0) return fail(BP_EINVAL, "mb %d is negative", mb);
+    if (causal) return fail(BP_ESTATE, "key padding lengths on a causal stage");
+    for (auto& s : slots)
+        if (s.live && s.mb == mb) return fail(BP_ESTATE, "micro-batch %d has a live stash", mb);
+    auto it = lens.find(mb);
+    if (!host) {
+        if (it != lens.end()) {
+            hipStreamSynchronize(stream);
+            hipFree(it->second);
+            lens.erase(it);
+        }
+        return BP_OK;
+    }
+    for (int b = 0; b < B; ++b)
+        if (host[b] < 1 || host[b] > S) return fail(BP_EINVAL, "length %d outside 1..%d", host[b], S);
+    int32_t* dev = nullptr;
+    if (it != lens.end()) dev = it->second;
+    else {
+        int rc = dev_alloc((void**)&dev, B * sizeof(int32_t));
+        if (rc) return rc;
+        lens[mb] = dev;
+    }
+    hipError_t e = hipMemcpyAsync(dev, host, B * sizeof(int32_t), hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(BP_EHIP, "set_seqlens: %s", hipGetErrorString(e));
+    return BP_OK;
+}
+
+// ------------------------------------------------------------------ stash slots
+
+int Stage::find_slot(int chunk, int mb) const {
+    for (size_t i = 0; i < slots.size(); ++i)
+        if (slots[i].live && slots[i].chunk == chunk && slots[i].mb == mb) return (int)i;
+    return -1;
+}
+
+int Stage::acquire_slot(int chunk, int mb, int* out) {
+    if (find_slot(chunk, mb) >= 0)
+        return fail(BP_ESTATE, "forward(chunk %d, mb %d) while its stash is still live", chunk, mb);
+    for (size_t i = 0; i < slots.size(); ++i) {
+        if (slots[i].live) continue;
+        if (!slots[i].buf) {
+            int rc = dev_alloc(&slots[i].buf, (size_t)L * s_layer_bytes);
+            if (rc) return rc;
+        }
+        slots[i].live = true; slots[i].chunk = chunk; slots[i].mb = mb;
+        *out = (int)i;
+        return BP_OK;
+    }
+    return fail(BP_ESTATE, "all %d stash slots are live (max_inflight)", max_inflight);
+}
+
+// ------------------------------------------------------------------ forward of one chunk
+
+#define BP_LAUNCH(expr)                                                                 \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess) return fail(BP_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+int Stage::gemm(const void* A, int lda, int a_t, const void* Bm, int ldb, int b_t, void* C, int ldc,
+                int M, int N, int K, const float* bias, const void* residual, int accumulate) {
+    GemmArgs g;
+    g.A = A; g.B = Bm; g.C = C; g.bias = bias; g.residual = residual;
+    g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+    g.a_t = a_t; g.b_t = b_t; g.accumulate = accumulate;
+    Scoped sc(this, BP_K_GEMM, 2.0 * M * N * K, 0);
+    BP_LAUNCH(launch_gemm(dtype, g, stream));
+    return BP_OK;
+}
+
+int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
+    if (chunk < 0 || chunk >= n_chunks) return fail(BP_EINVAL, "chunk %d out of range [0,%d)", chunk, n_chunks);
+    if (mb < 0) return fail(BP_EINVAL, "mb %d is negative", mb);
+    if (!act_in || !act_out) return fail(BP_EINVAL, "activation pointer is null");
+    if (act_in == act_out) return fail(BP_EINVAL, "act_in and act_out must not overlap");
+    int slot, rc;
+    if ((rc = acquire_slot(chunk, mb, &slot))) return rc;
+    auto it = lens.find(mb);
+    const int32_t* ln = it == lens.end() ? nullptr : it->second;
+    const double unit = (double)T * H * esz;   // bytes of one [T,H] tensor
+    const double attn_c = causal ? 0.5 : 1.0;
+
+    for (int l = 0; l < L; ++l) {
+        char* sb = (char*)slots[slot].buf + (size_t)l * s_layer_bytes;
+        const void* x = l == 0 ? act_in : (const void*)(sb + s_x);
+        void* z = l == L - 1 ? act_out : (void*)(sb + s_layer_bytes + s_x);
+        {   // a = LN1(x); layer 0 also keeps a copy of the caller's input for the backward
+            Scoped sc(this, BP_K_LN_FWD, 0, 2 * unit);
+            BP_LAUNCH(launch_ln_fwd(dtype, T, H, x, (const float*)param(chunk, l, BP_LN1_G),
+                                    (const float*)param(chunk, l, BP_LN1_B), eps, sb + s_a,
+                                    (float*)(sb + s_mean1), (float*)(sb + s_rstd1),
+                                    l == 0 ? sb + s_x : nullptr, stream));
+        }
+        if ((rc = gemm(sb + s_a, H, 0, param(chunk, l, BP_WQKV), 3 * H, 0, sb + s_qkv, 3 * H, T, 3 * H, H,
+                       (const float*)param(chunk, l, BP_BQKV), nullptr, 0))) return rc;
+        {
+            AttnArgs a{B, S, heads, d, causal ? 1 : 0, ln, sb + s_qkv, sb + s_ctx, (float*)(sb + s_lse),
+                       nullptr, nullptr, nullptr};
+            Scoped sc(this, BP_K_ATTN_FWD, 4.0 * T * S * H * attn_c, 0);
+            BP_LAUNCH(launch_attn_fwd(dtype, a, stream));
+        }
+        if ((rc = gemm(sb + s_ctx, H, 0, param(chunk, l, BP_WO), H, 0, sb + s_y, H, T, H, H,
+                       (const float*)param(chunk, l, BP_BO), x, 0))) return rc;
+        {
+            Scoped sc(this, BP_K_LN_FWD, 0, 2 * unit);
+            BP_LAUNCH(launch_ln_fwd(dtype, T, H, sb + s_y, (const float*)param(chunk, l, BP_LN2_G),
+                                    (const float*)param(chunk, l, BP_LN2_B), eps, sb + s_m,
+                                    (float*)(sb + s_mean2), (float*)(sb + s_rstd2), nullptr, stream));
+        }
+        if ((rc = gemm(sb + s_m, H, 0, param(chunk, l, BP_W1), F, 0, sb + s_u, F, T, F, H, nullptr, nullptr, 0)))
+            return rc;
+        {
+            Scoped sc(this, BP_K_GELU_FWD, 0, 2.0 * T * F * esz);
+            BP_LAUNCH(launch_gelu_fwd(dtype, T, F, sb + s_u, (const float*)param(chunk, l, BP_B1),
+                                      sb + s_g, stream));
+        }
+        if ((rc = gemm(sb + s_g, F, 0, param(chunk, l, BP_W2), H, 0, z, H, T, H, F,
+                       (const float*)param(chunk, l, BP_B2), sb + s_y, 0))) return rc;
+    }
+    return BP_OK;
+}
+
+// ------------------------------------------------------------------ backward of one chunk
+
+int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int dir) {
+    if (chunk < 0 || chunk >= n_chunks) return fail(BP_EINVAL, "chunk %d out of range [0,%d)", chunk, n_chunks);
+    if (dir != 0 && dir != 1) return fail(BP_EINVAL, "direction %d is not 0 or 1", dir);
+    if (!grad_out || !grad_in) return fail(BP_EINVAL, "gradient pointer is null");
+    const int slot = find_slot(chunk, mb);
+    if (slot < 0) return fail(BP_ESTATE, "backward(chunk %d, mb %d) without a stashed forward", chunk, mb);
+    auto it = lens.find(mb);
+    const int32_t* ln = it == lens.end() ? nullptr : it->second;
+    const double unit = (double)T * H * esz;
+    const double attn_c = causal ? 0.5 : 1.0;
+    int rc;
+
+    const void* dz = grad_out;
+    for (int l = L - 1; l >= 0; --l) {
+        char* sb = (char*)slots[slot].buf + (size_t)l * s_layer_bytes;
+        auto P = [&](int id) { return param(chunk, l, id); };
+        auto G = [&](int id) { return grad(dir, chunk, l, id); };
+        void* dx = l == 0 ? grad_in : ws_h3;
+        // z = y + g W2 + b2
+        if ((rc = gemm(dz, H, 0, P(BP_W2), H, 1, ws_big1, F, T, F, H, nullptr, nullptr, 0))) return rc;   // dg
+        if ((rc = gemm(sb + s_g, F, 1, dz, H, 0, G(BP_W2), H, F, H, T, nullptr, nullptr, 1))) return rc;   // dW2
+        {   // du = dg * gelu'(u + b1), db1
+            Scoped sc(this, BP_K_GELU_BWD, 0, 3.0 * T * F * esz);
+            BP_LAUNCH(launch_gelu_bwd(dtype, T, F, ws_big1, sb + s_u, (const float*)P(BP_B1), ws_big1,
+                                      G(BP_B1), ws_colsum, stream));
+        }
+        if ((rc = gemm(ws_big1, F, 0, P(BP_W1), F, 1, ws_h1, H, T, H, F, nullptr, nullptr, 0))) return rc;   // dm
+        if ((rc = gemm(sb + s_m, H, 1, ws_big1, F, 0, G(BP_W1), F, H, F, T, nullptr, nullptr, 1))) return rc; // dW1
+        {   // dy = dz + LN2bwd(dm)
+            Scoped sc(this, BP_K_LN_BWD, 0, 4 * unit);
+            BP_LAUNCH(launch_ln_bwd_rows(dtype, T, H, ws_h1, sb + s_y, (const float*)(sb + s_mean2),
+                                         (const float*)(sb + s_rstd2), (const float*)P(BP_LN2_G), dz,
+                                         ws_h2, stream));
+        }
+        {   // dgamma2, dbeta2, db2, dbo
+            Scoped sc(this, BP_K_COLSUM, 0, 0);
+            BP_LAUNCH(launch_colsum(dtype, T, H, ws_h1, sb + s_y, (const float*)(sb + s_mean2),
+                                    (const float*)(sb + s_rstd2), G(BP_LN2_B), G(BP_LN2_G), ws_colsum, stream));
+            BP_LAUNCH(launch_colsum(dtype, T, H, dz, nullptr, nullptr, nullptr, G(BP_B2), nullptr, ws_colsum, stream));
+            BP_LAUNCH(launch_colsum(dtype, T, H, ws_h2, nullptr, nullptr, nullptr, G(BP_BO), nullptr, ws_colsum, stream));
+        }
+        // y = x + ctx Wo + bo
+        if ((rc = gemm(ws_h2, H, 0, P(BP_WO), H, 1, ws_h1, H, T, H, H, nullptr, nullptr, 0))) return rc;      // dctx
+        if ((rc = gemm(sb + s_ctx, H, 1, ws_h2, H, 0, G(BP_WO), H, H, H, T, nullptr, nullptr, 1))) return rc;  // dWo
+        {
+            AttnArgs a{B, S, heads, d, causal ? 1 : 0, ln, sb + s_qkv, sb + s_ctx, (float*)(sb + s_lse),
+                       ws_h1, ws_big2, ws_delta};
+            Scoped sc(this, BP_K_ATTN_BWD, 8.0 * T * S * H * attn_c, 0);
+            BP_LAUNCH(launch_attn_bwd(dtype, a, stream));
+        }
+        // qkv = a Wqkv + bqkv
+        if ((rc = gemm(ws_big2, 3 * H, 0, P(BP_WQKV), 3 * H, 1, ws_h1, H, T, H, 3 * H, nullptr, nullptr, 0))) return rc;  // da
+        if ((rc = gemm(sb + s_a, H, 1, ws_big2, 3 * H, 0, G(BP_WQKV), 3 * H, H, 3 * H, T, nullptr, nullptr, 1))) return rc;
+        {
+            Scoped sc(this, BP_K_COLSUM, 0, 0);
+            BP_LAUNCH(launch_colsum(dtype, T, 3 * H, ws_big2, nullptr, nullptr, nullptr, G(BP_BQKV), nullptr,
+                                    ws_colsum, stream));
+            BP_LAUNCH(launch_colsum(dtype, T, H, ws_h1, sb + s_x, (const float*)(sb + s_mean1),
+                                    (const float*)(sb + s_rstd1), G(BP_LN1_B), G(BP_LN1_G), ws_colsum, stream));
+        }
+        {   // dx = dy + LN1bwd(da)
+            Scoped sc(this, BP_K_LN_BWD, 0, 4 * unit);
+            BP_LAUNCH(launch_ln_bwd_rows(dtype, T, H, ws_h1, sb + s_x, (const float*)(sb + s_mean1),
+                                         (const float*)(sb + s_rstd1), (const float*)P(BP_LN1_G), ws_h2,
+                                         dx, stream));
+        }
+        dz = dx;
+    }
+    slots[slot].live = false;
+    return BP_OK;
+}
+
+}  // namespace bp
+
+// ====================================================================== C ABI
+
+using bp::Stage;
+using bp::fail;
+
+extern "C" {
+
+int bp_stage_init(bp_stage_t** out, int layers, int hidden, int heads, int seq, int microbatch, int causal) {
+    return Stage::create((Stage**)out, layers, hidden, heads, seq, microbatch, causal, nullptr);
+}
+
+int bp_stage_init_ex(bp_stage_t** out, int layers, int hidden, int heads, int seq, int microbatch,
+                     int causal, const bp_opts* opts) {
+    return Stage::create((Stage**)out, layers, hidden, heads, seq, microbatch, causal, opts);
+}
+
+int bp_stage_destroy(bp_stage_t* st) {
+    delete (Stage*)st;
+    return BP_OK;
+}
+
+#define BP_ST(st) \
+    Stage* s_ = (Stage*)(st); \
+    if (!s_) return fail(BP_EINVAL, "stage handle is null")
+
+int bp_stage_set_param(bp_stage_t* st, int chunk, int layer, int id, const float* host, size_t n) {
+    BP_ST(st);
+    return s_->set_param(chunk, layer, id, host, n);
+}
+int bp_stage_get_grad(bp_stage_t* st, int chunk, int layer, int id, float* host, size_t n) {
+    BP_ST(st);
+    return s_->get_grad(chunk, layer, id, host, n);
+}
+int bp_stage_zero_grad(bp_stage_t* st) {
+    BP_ST(st);
+    return s_->zero_grad();
+}
+int bp_stage_set_seqlens(bp_stage_t* st, int mb, const int32_t* lens) {
+    BP_ST(st);
+    return s_->set_seqlens(mb, lens);
+}
+int bp_stage_forward(bp_stage_t* st, int chunk, int mb, const void* act_in, void* act_out) {
+    BP_ST(st);
+    return s_->forward(chunk, mb, act_in, act_out);
+}
+int bp_stage_backward(bp_stage_t* st, int chunk, int mb, const void* grad_out, void* grad_in) {
+    BP_ST(st);
+    return s_->backward(chunk, mb, grad_out, grad_in, 0);
+}
+int bp_stage_backward_dir(bp_stage_t* st, int chunk, int mb, const void* grad_out, void* grad_in, int dir) {
+    BP_ST(st);
+    return s_->backward(chunk, mb, grad_out, grad_in, dir);
+}
+
+int bp_prof_enable(bp_stage_t* st, int on) {
+    BP_ST(st);
+    hipStreamSynchronize(s_->stream);
+    s_->prof.reset();
+    s_->prof.on = on != 0;
+    return BP_OK;
+}
+
+int bp_prof_get(bp_stage_t* st, int kid, double* ms, long long* launches, double* flops, double* bytes) {
+    BP_ST(st);
+    if (kid < 0 || kid >= BP_N_KERNEL_IDS) return fail(BP_EINVAL, "kernel id %d out of range", kid);
+    hipStreamSynchronize(s_->stream);
+    s_->prof.collect();
+    if (ms) *ms = s_->prof.ms_total[kid];
+    if (launches) *launches = s_->prof.launches[kid];
+    if (flops) *flops = s_->prof.flops_total[kid];
+    if (bytes) *bytes = s_->prof.bytes_total[kid];
+    return BP_OK;
+}
+
+const char* bp_last_error(void) { return bp::last_error(); }
+const char* bp_version(void) { return "bitpipe-stage-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,467 @@
+// Bandwidth-bound kernels of the stage: LayerNorm forward/backward (+ residual-gradient add),
+// bias+GELU forward/backward, column reductions for bias and LayerNorm parameter gradients,
+// the synthetic loss, and small utilities.  All are one pass over their data with 16-byte
+// accesses per lane; statistics and math are fp32 whatever the storage type.
+#include "bp_kernels.h"
+#include "bp_device.h"
+
+namespace bp {
+
+// ------------------------------------------------------------------ LayerNorm forward
+// One 64-lane wave per row; the row lives in registers (NP passes of 64 lanes x 8 columns).
+template <typename T, int NP>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x,
+                                                     const float* __restrict__ gamma,
+                                                     const float* __restrict__ beta,
+                                                     T* __restrict__ out, float* __restrict__ mean,
+                                                     float* __restrict__ rstd, T* __restrict__ xcopy,
+                                                     int rows, int H, float eps) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const T* xr = x + (size_t)row * H;
+    float v[NP][8];
+    float s = 0.f;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int col = (p * 64 + lane) * 8;
+        if (col < H) {
+            load8(xr + col, v[p]);
+            if (xcopy) store8(xcopy + (size_t)row * H + col, v[p]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += v[p][i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[p][i] = 0.f;
+        }
+    }
+    const float mu = wave_sum(s) / (float)H;
+    float q = 0.f;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int col = (p * 64 + lane) * 8;
+        if (col < H) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { const float d = v[p][i] - mu; q += d * d; }
+        }
+    }
+    const float rs = rsqrtf(wave_sum(q) / (float)H + eps);
+    if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int col = (p * 64 + lane) * 8;
+        if (col < H) {
+            float g[8], b[8], o[8];
+            load8(gamma + col, g);
+            load8(beta + col, b);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[i] = (v[p][i] - mu) * rs * g[i] + b[i];
+            store8(out + (size_t)row * H + col, o);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ LayerNorm backward (rows)
+// dx = res + rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)), dxhat = dout * gamma.
+template <typename T, int NP>
+__global__ __launch_bounds__(256) void ln_bwd_rows_kernel(const T* __restrict__ dout,
+                                                          const T* __restrict__ x,
+                                                          const float* __restrict__ mean,
+                                                          const float* __restrict__ rstd,
+                                                          const float* __restrict__ gamma,
+                                                          const T* __restrict__ res,
+                                                          T* __restrict__ dx, int rows, int H) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const size_t base = (size_t)row * H;
+    const float mu = mean[row], rs = rstd[row];
+    float xh[NP][8], dh[NP][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int col = (p * 64 + lane) * 8;
+        if (col < H) {
+            float g[8];
+            load8(x + base + col, xh[p]);
+            load8(dout + base + col, dh[p]);
+            load8(gamma + col, g);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                xh[p][i] = (xh[p][i] - mu) * rs;
+                dh[p][i] *= g[i];
+                s1 += dh[p][i];
+                s2 += dh[p][i] * xh[p][i];
+            }
+        }
+    }
+    s1 = wave_sum(s1) / (float)H;
+    s2 = wave_sum(s2) / (float)H;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int col = (p * 64 + lane) * 8;
+        if (col < H) {
+            float r[8], o[8];
+            if (res) load8(res + base + col, r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                o[i] = rs * (dh[p][i] - s1 - xh[p][i] * s2);
+                if (res) o[i] += r[i];
+            }
+            store8(dx + base + col, o);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ column reductions
+// Block = 4 waves covering 512 columns x kColsumRows rows; wave w takes rows w, w+4, ...
+// Partials are combined across the waves in LDS and written per row chunk; a second kernel
+// folds the chunks in a fixed order, so the result does not depend on scheduling.
+template <typename T, bool WITH_X>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ A,
+                                                             const T* __restrict__ X,
+                                                             const float* __restrict__ mean,
+                                                             const float* __restrict__ rstd,
+                                                             float* __restrict__ part, int rows,
+                                                             int N) {
+    __shared__ float red[2][4][512];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int col = blockIdx.x * 512 + lane * 8;
+    const int r0 = blockIdx.y * kColsumRows;
+    const int r1 = min(r0 + kColsumRows, rows);
+    float sa[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (col < N) {
+        for (int r = r0 + w; r < r1; r += 4) {
+            float a[8];
+            load8(A + (size_t)r * N + col, a);
+            if (WITH_X) {
+                float xv[8];
+                load8(X + (size_t)r * N + col, xv);
+                const float mu = mean[r], rs = rstd[r];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) sx[i] += a[i] * (xv[i] - mu) * rs;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sa[i] += a[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        red[0][w][lane * 8 + i] = sa[i];
+        if (WITH_X) red[1][w][lane * 8 + i] = sx[i];
+    }
+    __syncthreads();
+    const int nout = WITH_X ? 2 : 1;
+    for (int e = threadIdx.x; e < 512 * nout; e += 256) {
+        const int o = e / 512, c = e % 512;
+        const int gc = blockIdx.x * 512 + c;
+        if (gc < N) {
+            const float s = (red[o][0][c] + red[o][1][c]) + (red[o][2][c] + red[o][3][c]);
+            part[((size_t)blockIdx.y * nout + o) * N + gc] = s;
+        }
+    }
+}
+
+// out_k[c] += sum over chunks of part[chunk][k][c]
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part,
+                                                           int chunks, int nout, int N,
+                                                           float* __restrict__ out0,
+                                                           float* __restrict__ out1) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int o = blockIdx.y;
+    if (c >= N) return;
+    float s = 0.f;
+    for (int k = 0; k < chunks; ++k) s += part[((size_t)k * nout + o) * N + c];
+    float* out = o == 0 ? out0 : out1;
+    out[c] += s;
+}
+
+// ------------------------------------------------------------------ bias + GELU
+__device__ __forceinline__ float gelu_tanh_part(float x) {
+    // tanh(sqrt(2/pi) (x + 0.044715 x^3)) via exp; exact limits for large |x|
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    return 1.f - 2.f / (1.f + __expf(2.f * u));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_fwd_kernel(const T* __restrict__ u,
+                                                       const float* __restrict__ bias,
+                                                       T* __restrict__ g, int rows, int F) {
+    const int vec_per_row = F / 8;
+    const size_t total = (size_t)rows * vec_per_row;
+    for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < total; v += (size_t)gridDim.x * 256) {
+        const int col = (int)(v % vec_per_row) * 8;
+        float a[8], b[8], o[8];
+        load8(u + v * 8, a);
+        load8(bias + col, b);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float x = a[i] + b[i];
+            o[i] = 0.5f * x * (1.f + gelu_tanh_part(x));
+        }
+        store8(g + v * 8, o);
+    }
+}
+
+// du = dg * gelu'(u + b); partial column sums of du per row chunk (same scheme as colsum).
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* dg,   // may alias du
+                                                       const T* __restrict__ u,
+                                                       const float* __restrict__ bias,
+                                                       T* du, float* __restrict__ part,
+                                                       int rows, int F) {
+    __shared__ float red[4][512];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int col = blockIdx.x * 512 + lane * 8;
+    const int r0 = blockIdx.y * kColsumRows;
+    const int r1 = min(r0 + kColsumRows, rows);
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (col < F) {
+        float b[8];
+        load8(bias + col, b);
+        for (int r = r0 + w; r < r1; r += 4) {
+            float a[8], d[8], o[8];
+            load8(u + (size_t)r * F + col, a);
+            load8(dg + (size_t)r * F + col, d);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float x = a[i] + b[i];
+                const float t = gelu_tanh_part(x);
+                const float dudx = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
+                const float gp = 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * dudx;
+                o[i] = d[i] * gp;
+            }
+            store8(du + (size_t)r * F + col, o);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] += o[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) red[w][lane * 8 + i] = acc[i];
+    __syncthreads();
+    for (int c = threadIdx.x; c < 512; c += 256) {
+        const int gc = blockIdx.x * 512 + c;
+        if (gc < F)
+            part[(size_t)blockIdx.y * F + gc] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+    }
+}
+
+// ------------------------------------------------------------------ loss
+template <typename T>
+__global__ __launch_bounds__(256) void loss_partial_kernel(const T* __restrict__ z,
+                                                           const T* __restrict__ y, float scale,
+                                                           T* __restrict__ grad,
+                                                           float* __restrict__ part, size_t n) {
+    __shared__ float red[4];
+    float s = 0.f;
+    const size_t nv = n / 8;
+    for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < nv; v += (size_t)gridDim.x * 256) {
+        float a[8], b[8], o[8];
+        load8(z + v * 8, a);
+        load8(y + v * 8, b);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float d = a[i] - b[i];
+            s += d * d;
+            o[i] = d * scale;
+        }
+        store8(grad + v * 8, o);
+    }
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(256) void loss_final_kernel(const float* __restrict__ part, int nparts,
+                                                         float scale, float* __restrict__ out) {
+    __shared__ float red[4];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < nparts; i += 256) s += part[i];
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) out[0] = 0.5f * scale * ((red[0] + red[1]) + (red[2] + red[3]));
+}
+
+// ------------------------------------------------------------------ utilities
+__global__ __launch_bounds__(256) void fill_f32_kernel(float* p, size_t n, float v) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+        p[i] = v;
+}
+__global__ __launch_bounds__(256) void add_f32_kernel(float* dst, const float* src, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+        dst[i] += src[i];
+}
+template <typename T>
+__global__ __launch_bounds__(256) void cast_from_f32_kernel(const float* src, T* dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256)
+        dst[i] = from_float<T>(src[i]);
+}
+
+// ------------------------------------------------------------------ launchers
+static inline int grid_for(size_t work_items, int per_block, int cap = 256 * 16) {
+    size_t b = (work_items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    return (int)(b > (size_t)cap ? cap : b);
+}
+
+template <typename T>
+static hipError_t ln_fwd_dispatch(int T_, int H, const T* x, const float* gamma, const float* beta,
+                                  float eps, T* out, float* mean, float* rstd, T* xcopy,
+                                  hipStream_t s) {
+    const int np = (H + 511) / 512;
+    dim3 grid((T_ + 3) / 4), block(256);
+#define BP_LN_CASE(NPV)                                                                        \
+    if (np <= NPV) {                                                                           \
+        hipLaunchKernelGGL((ln_fwd_kernel<T, NPV>), grid, block, 0, s, x, gamma, beta, out,    \
+                           mean, rstd, xcopy, T_, H, eps);                                     \
+        return hipGetLastError();                                                              \
+    }
+    BP_LN_CASE(1) BP_LN_CASE(2) BP_LN_CASE(4) BP_LN_CASE(6) BP_LN_CASE(8) BP_LN_CASE(10)
+    BP_LN_CASE(16)
+#undef BP_LN_CASE
+    return hipErrorInvalidValue;
+}
+
+template <typename T>
+static hipError_t ln_bwd_dispatch(int T_, int H, const T* dout, const T* x, const float* mean,
+                                  const float* rstd, const float* gamma, const T* res, T* dx,
+                                  hipStream_t s) {
+    const int np = (H + 511) / 512;
+    dim3 grid((T_ + 3) / 4), block(256);
+#define BP_LN_CASE(NPV)                                                                        \
+    if (np <= NPV) {                                                                           \
+        hipLaunchKernelGGL((ln_bwd_rows_kernel<T, NPV>), grid, block, 0, s, dout, x, mean,     \
+                           rstd, gamma, res, dx, T_, H);                                       \
+        return hipGetLastError();                                                              \
+    }
+    BP_LN_CASE(1) BP_LN_CASE(2) BP_LN_CASE(4) BP_LN_CASE(6) BP_LN_CASE(8) BP_LN_CASE(10)
+    BP_LN_CASE(16)
+#undef BP_LN_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_ln_fwd(int dtype, int T, int H, const void* x, const float* gamma,
+                         const float* beta, float eps, void* out, float* mean, float* rstd,
+                         void* xcopy, hipStream_t s) {
+    if (H % 8 || H > 8192 || T <= 0) return hipErrorInvalidValue;
+    if (dtype == BF16)
+        return ln_fwd_dispatch<bf16_t>(T, H, (const bf16_t*)x, gamma, beta, eps, (bf16_t*)out, mean,
+                                       rstd, (bf16_t*)xcopy, s);
+    return ln_fwd_dispatch<float>(T, H, (const float*)x, gamma, beta, eps, (float*)out, mean, rstd,
+                                  (float*)xcopy, s);
+}
+
+hipError_t launch_ln_bwd_rows(int dtype, int T, int H, const void* dout, const void* x,
+                              const float* mean, const float* rstd, const float* gamma,
+                              const void* res, void* dx, hipStream_t s) {
+    if (H % 8 || H > 8192 || T <= 0) return hipErrorInvalidValue;
+    if (dtype == BF16)
+        return ln_bwd_dispatch<bf16_t>(T, H, (const bf16_t*)dout, (const bf16_t*)x, mean, rstd, gamma,
+                                       (const bf16_t*)res, (bf16_t*)dx, s);
+    return ln_bwd_dispatch<float>(T, H, (const float*)dout, (const float*)x, mean, rstd, gamma,
+                                  (const float*)res, (float*)dx, s);
+}
+
+template <typename T>
+static hipError_t colsum_dispatch(int T_, int N, const T* A, const T* X, const float* mean,
+                                  const float* rstd, float* out_a, float* out_ax, float* ws,
+                                  hipStream_t s) {
+    const int chunks = (int)colsum_chunks(T_);
+    dim3 grid((N + 511) / 512, chunks), block(256);
+    if (X)
+        hipLaunchKernelGGL((colsum_partial_kernel<T, true>), grid, block, 0, s, A, X, mean, rstd, ws,
+                           T_, N);
+    else
+        hipLaunchKernelGGL((colsum_partial_kernel<T, false>), grid, block, 0, s, A, X, mean, rstd,
+                           ws, T_, N);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int nout = X ? 2 : 1;
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((N + 255) / 256, nout), block, 0, s, ws, chunks,
+                       nout, N, out_a, out_ax);
+    return hipGetLastError();
+}
+
+hipError_t launch_colsum(int dtype, int T, int N, const void* A, const void* X, const float* mean,
+                         const float* rstd, float* out_a, float* out_ax, float* ws,
+                         hipStream_t s) {
+    if (N % 8 || T <= 0) return hipErrorInvalidValue;
+    if (dtype == BF16)
+        return colsum_dispatch<bf16_t>(T, N, (const bf16_t*)A, (const bf16_t*)X, mean, rstd, out_a,
+                                       out_ax, ws, s);
+    return colsum_dispatch<float>(T, N, (const float*)A, (const float*)X, mean, rstd, out_a, out_ax,
+                                  ws, s);
+}
+
+hipError_t launch_gelu_fwd(int dtype, int T, int F, const void* u, const float* bias, void* g,
+                           hipStream_t s) {
+    if (F % 8 || T <= 0) return hipErrorInvalidValue;
+    const int grid = grid_for((size_t)T * F / 8, 256, 256 * 32);
+    if (dtype == BF16)
+        hipLaunchKernelGGL((gelu_fwd_kernel<bf16_t>), dim3(grid), dim3(256), 0, s, (const bf16_t*)u,
+                           bias, (bf16_t*)g, T, F);
+    else
+        hipLaunchKernelGGL((gelu_fwd_kernel<float>), dim3(grid), dim3(256), 0, s, (const float*)u,
+                           bias, (float*)g, T, F);
+    return hipGetLastError();
+}
+
+hipError_t launch_gelu_bwd(int dtype, int T, int F, const void* dg, const void* u,
+                           const float* bias, void* du, float* dbias, float* ws, hipStream_t s) {
+    if (F % 8 || T <= 0) return hipErrorInvalidValue;
+    const int chunks = (int)colsum_chunks(T);
+    dim3 grid((F + 511) / 512, chunks), block(256);
+    if (dtype == BF16)
+        hipLaunchKernelGGL((gelu_bwd_kernel<bf16_t>), grid, block, 0, s, (const bf16_t*)dg,
+                           (const bf16_t*)u, bias, (bf16_t*)du, ws, T, F);
+    else
+        hipLaunchKernelGGL((gelu_bwd_kernel<float>), grid, block, 0, s, (const float*)dg,
+                           (const float*)u, bias, (float*)du, ws, T, F);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((F + 255) / 256, 1), block, 0, s, ws, chunks, 1, F,
+                       dbias, (float*)nullptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_loss(int dtype, size_t n, const void* z, const void* target, float scale,
+                       void* grad, float* loss_out, float* ws, hipStream_t s) {
+    if (n % 8) return hipErrorInvalidValue;
+    const int grid = grid_for(n / 8, 256, 1024);
+    if (dtype == BF16)
+        hipLaunchKernelGGL((loss_partial_kernel<bf16_t>), dim3(grid), dim3(256), 0, s,
+                           (const bf16_t*)z, (const bf16_t*)target, scale, (bf16_t*)grad, ws, n);
+    else
+        hipLaunchKernelGGL((loss_partial_kernel<float>), dim3(grid), dim3(256), 0, s,
+                           (const float*)z, (const float*)target, scale, (float*)grad, ws, n);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(loss_final_kernel, dim3(1), dim3(256), 0, s, ws, grid, scale, loss_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_f32_kernel, dim3(grid_for(n, 256 * 4)), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+hipError_t launch_add_f32(float* dst, const float* src, size_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(add_f32_kernel, dim3(grid_for(n, 256 * 4)), dim3(256), 0, s, dst, src, n);
+    return hipGetLastError();
+}
+hipError_t launch_cast_from_f32(int dtype, const float* src, void* dst, size_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    const int grid = grid_for(n, 256 * 4);
+    if (dtype == BF16)
+        hipLaunchKernelGGL((cast_from_f32_kernel<bf16_t>), dim3(grid), dim3(256), 0, s, src,
+                           (bf16_t*)dst, n);
+    else
+        hipLaunchKernelGGL((cast_from_f32_kernel<float>), dim3(grid), dim3(256), 0, s, src,
+                           (float*)dst, n);
+    return hipGetLastError();
+}
+
+}  // namespace bp
