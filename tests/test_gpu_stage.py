@@ -22,7 +22,7 @@ def test_cfg0_tiny_gpt_fp32_full():
     ("bert_full_len", dict(layers=1, hidden=128, heads=2, seq=96, microbatch=2, causal=False)),
 ])
 def test_small_bf16_stages(name, kw):
-    cfg = si.scaled(si.CONFIGS[1], name="small_" + name, n_micro=2, len_lo=0, len_hi=0, **kw)
+    cfg = si.scaled(si.CONFIGS[1], name="small_" + name, n_micro=2, **kw)
     errs = hz.run_fwd_bwd_parity(cfg, ln_jitter=0.1)
     worst = max(errs.items(), key=lambda kv: kv[1])
     print(name, "worst", worst)
