@@ -65,6 +65,28 @@ def layer_norm_bwd(dout, xhat, rstd, gamma):
     return dx, dgamma, dbeta
 
 
+def linear_fwd(x, W, b=None, residual=None):
+    """y = x W (+ b) (+ residual) with W row-major [in, out]."""
+    y = x @ W
+    if b is not None:
+        y = y + b
+    if residual is not None:
+        y = y + residual
+    return y
+
+
+def linear_dgrad(dy, W):
+    """dx = dy W^T."""
+    return dy @ W.T
+
+
+def linear_wgrad(x, dy):
+    """dW = x^T dy over all rows (tokens); db = column sums of dy."""
+    x2 = x.reshape(-1, x.shape[-1])
+    d2 = dy.reshape(-1, dy.shape[-1])
+    return x2.T @ d2, d2.sum(axis=0)
+
+
 def gelu(x):
     """tanh-form GELU: 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3)))."""
     return 0.5 * x * (1.0 + np.tanh(_GELU_C * (x + _GELU_A * x ** 3)))

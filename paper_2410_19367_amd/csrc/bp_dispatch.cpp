@@ -4,6 +4,7 @@
 namespace bp {
 
 hipError_t launch_gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
+    if (dtype == BF16 && gemm_mfma_supported(g)) return launch_gemm_mfma(g, stream);
     return launch_gemm_generic(dtype, g, stream);
 }
 

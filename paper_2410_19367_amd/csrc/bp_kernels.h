@@ -27,6 +27,8 @@ struct GemmArgs {
 // picks the MFMA kernel when the shape allows it, else the generic one
 hipError_t launch_gemm(int dtype, const GemmArgs& g, hipStream_t stream);
 hipError_t launch_gemm_generic(int dtype, const GemmArgs& g, hipStream_t stream);
+bool gemm_mfma_supported(const GemmArgs& g);                       // bf16 only
+hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t stream);
 
 // rows kept per partial of a column reduction
 constexpr int kColsumRows = 32;

@@ -1,0 +1,259 @@
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation) for the
+// three shapes of a linear layer: forward Y = X W (+b)(+res), dgrad dX = dY W^T, wgrad dW += X^T dY.
+//
+// A block computes a BM x BN tile of C, stepping over K in slices of BK = 64.  Each slice of
+// op(A) and op(B) is copied global -> registers -> LDS as 16-byte chunks with no reshaping:
+//   * an operand whose contraction index is contiguous in memory ("k-major": X, dY in dgrad,
+//     W in dgrad) is stored as [row][64 k] and read back with one ds_read_b128 per fragment;
+//   * an operand whose row index is contiguous ("r-major": W in forward, X^T and dY in wgrad)
+//     is stored as [k][rows] and read back with the LDS transpose read ds_read_b64_tr_b16,
+//     which hands each lane four consecutive k of one row.
+// Both layouts XOR-swizzle the chunk index so fragment reads spread over all LDS banks.
+// Two LDS stages: the slice k+1 is written while slice k feeds the MFMAs, one barrier per slice.
+#include "bp_kernels.h"
+#include "bp_device.h"
+
+namespace bp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 64;
+
+// ---- LDS layouts (byte offsets inside one operand tile)
+// k-major tile [R][64]: 128 bytes per row, chunk c (8 elements) of a row stored at c ^ ((row>>1)&7)
+__device__ __forceinline__ int kmajor_off(int row, int chunk) {
+    return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
+}
+// r-major tile [64][R]: 2R bytes per k-row, 16-byte chunk c stored at c ^ ((k&3)<<2)
+template <int R>
+__device__ __forceinline__ int rmajor_off(int k, int chunk) {
+    return k * (2 * R) + ((chunk ^ ((k & 3) << 2)) << 4);
+}
+
+template <int R> constexpr int tile_bytes() { return R * BK * 2; }
+
+// ---- global -> registers -> LDS for one operand slice.
+// NT threads copy R*8 chunks of 16 bytes; CH = chunks per thread.
+template <int R, int NT, bool RMAJOR, bool RAGGED>
+struct TileLoader {
+    static constexpr int CH = R * 8 / NT;
+    uint4 regs[CH];
+
+    // rows_valid: number of valid rows of this tile (M or N remainder); k_valid: valid k in slice
+    __device__ __forceinline__ void load(const bf16_t* __restrict__ base, int ld, int rows_valid,
+                                         int k_valid) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int q = threadIdx.x + i * NT;
+            int row, k;
+            if (RMAJOR) { k = q / (R / 8); row = (q % (R / 8)) * 8; }
+            else { row = q >> 3; k = (q & 7) * 8; }
+            const bf16_t* p = RMAJOR ? base + (size_t)k * ld + row : base + (size_t)row * ld + k;
+            if (RAGGED) {
+                // chunks are 8 elements along the contiguous axis; shapes are multiples of 8 there
+                const bool ok = row < rows_valid && k < k_valid;
+                regs[i] = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+            } else {
+                regs[i] = *reinterpret_cast<const uint4*>(p);
+            }
+        }
+    }
+    __device__ __forceinline__ void store(char* lds) const {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int q = threadIdx.x + i * NT;
+            int off;
+            if (RMAJOR) off = rmajor_off<R>(q / (R / 8), q % (R / 8));
+            else off = kmajor_off(q >> 3, q & 7);
+            *reinterpret_cast<uint4*>(lds + off) = regs[i];
+        }
+    }
+};
+
+// ---- fragment read: 8 consecutive k (k16 step kk, half h = lane/32) of row (row0 + lane%32)
+template <int R, bool RMAJOR>
+__device__ __forceinline__ bf16x8 read_frag(const char* lds, int row0, int kk, int lane) {
+    const int h = lane >> 5;
+    if (!RMAJOR) {
+        const int row = row0 + (lane & 31);
+        return *reinterpret_cast<const bf16x8*>(lds + kmajor_off(row, kk * 2 + h));
+    } else {
+        // transpose read: within a group of 16 lanes, lane i receives element (i%4) of the four
+        // 8-byte rows addressed by lanes r*4 + i/4 (r = 0..3).  Lane j = 4r + q therefore points
+        // at k-row (k0 + r), elements [col0 + 4q, col0 + 4q + 4), and lane i ends up with
+        // k0..k0+3 of column col0 + i.
+        const int i = lane & 15, g2 = (lane >> 4) & 1;
+        const int r = i >> 2, q = i & 3;
+        const int col = row0 + 16 * g2 + 4 * q;       // element index along the r-major row
+        const int chunk = col >> 3, byte = (col & 7) * 2;
+        const int k0 = kk * 16 + 8 * h;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(lds + rmajor_off<R>(k0 + r, chunk) + byte));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(lds + rmajor_off<R>(k0 + 4 + r, chunk) + byte));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, v);
+    }
+}
+
+// ---- the kernel
+// WM x WN waves, each owning a (BM/WM) x (BN/WN) sub-tile made of 32x32 MFMA tiles.
+template <int BM, int BN, int WM, int WN, bool A_RMAJOR, bool B_RMAJOR, bool RAGGED>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // MFMA tiles per wave
+    constexpr int A_BYTES = tile_bytes<BM>(), B_BYTES = tile_bytes<BN>();
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    // Blocks are dealt round-robin to the 8 XCDs; give each XCD a contiguous band of tiles so the
+    // blocks sharing an L2 also share rows of A, and walk tiles column-first inside the band.
+    const int nblk = tiles_m * tiles_n;
+    int bid = blockIdx.x;
+    if (nblk % 8 == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
+    const int tm = bid / tiles_n, tn = bid % tiles_n;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const bf16_t* A = (const bf16_t*)g.A;
+    const bf16_t* B = (const bf16_t*)g.B;
+    // op(A) rows are m; k-major: A[m*lda + k]; r-major (a_t): A[k*lda + m]
+    const bf16_t* a_base = A_RMAJOR ? A + m0 : A + (size_t)m0 * g.lda;
+    // op(B) rows are n; k-major (b_t): B[n*ldb + k]; r-major: B[k*ldb + n]
+    const bf16_t* b_base = B_RMAJOR ? B + n0 : B + (size_t)n0 * g.ldb;
+    const size_t a_step = A_RMAJOR ? (size_t)BK * g.lda : BK;
+    const size_t b_step = B_RMAJOR ? (size_t)BK * g.ldb : BK;
+    const int m_valid = g.M - m0, n_valid = g.N - n0;
+
+    TileLoader<BM, NT, A_RMAJOR, RAGGED> la;
+    TileLoader<BN, NT, B_RMAJOR, RAGGED> lb;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = (g.K + BK - 1) / BK;
+    la.load(a_base, g.lda, m_valid, g.K);
+    lb.load(b_base, g.ldb, n_valid, g.K);
+    la.store(smem);
+    lb.store(smem + A_BYTES);
+    if (nk > 1) {
+        la.load(a_base + a_step, g.lda, m_valid, g.K - BK);
+        lb.load(b_base + b_step, g.ldb, n_valid, g.K - BK);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        char* sa = smem + cur * (A_BYTES + B_BYTES);
+        char* sb = sa + A_BYTES;
+        // slice kt+1 (already in registers) goes to the other stage; nobody reads that stage any
+        // more: every wave has passed the barrier that ended the previous iteration
+        if (kt + 1 < nk) {
+            char* na = smem + (cur ^ 1) * (A_BYTES + B_BYTES);
+            la.store(na);
+            lb.store(na + A_BYTES);
+        }
+        if (kt + 2 < nk) {
+            la.load(a_base + (size_t)(kt + 2) * a_step, g.lda, m_valid, g.K - (kt + 2) * BK);
+            lb.load(b_base + (size_t)(kt + 2) * b_step, g.ldb, n_valid, g.K - (kt + 2) * BK);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = read_frag<BM, A_RMAJOR>(sa, wm * (BM / WM) + i * 32, kk, lane);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[j] = read_frag<BN, B_RMAJOR>(sb, wn * (BN / WN) + j * 32, kk, lane);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue.  Accumulator v of lane l holds C[8*(v/4) + 4*(l/32) + v%4][l%32] of its tile.
+    const int col_l = lane & 31, row_l = 4 * (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * (BN / WN) + j * 32 + col_l;
+        if (RAGGED && n >= g.N) continue;
+        const float bias = (!g.accumulate && g.bias) ? g.bias[n] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+                if (RAGGED && m >= g.M) continue;
+                const size_t o = (size_t)m * g.ldc + n;
+                if (g.accumulate) {
+                    ((float*)g.C)[o] += acc[i][j][v];
+                } else {
+                    float r = acc[i][j][v] + bias;
+                    if (g.residual) r += (float)((const bf16_t*)g.residual)[o];
+                    ((bf16_t*)g.C)[o] = (bf16_t)r;
+                }
+            }
+        }
+    }
+}
+
+// ---- host-side selection
+template <int BM, int BN, int WM, int WN, bool RAGGED>
+static hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const dim3 grid(tiles_m * tiles_n), block(WM * WN * 64);
+    const size_t smem = 2 * (size_t)(tile_bytes<BM>() + tile_bytes<BN>());
+#define BP_GEMM_LAUNCH(AR, BR)                                                                   \
+    do {                                                                                         \
+        auto kern = gemm_mfma_kernel<BM, BN, WM, WN, AR, BR, RAGGED>;                            \
+        static bool attr_set = false;   /* once per instantiation */                             \
+        if (smem > 64 * 1024 && !attr_set) {                                                     \
+            hipError_t e = hipFuncSetAttribute((const void*)kern,                                \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+            if (e != hipSuccess) return e;                                                       \
+            attr_set = true;                                                                     \
+        }                                                                                        \
+        hipLaunchKernelGGL(kern, grid, block, smem, s, g, tiles_m, tiles_n);                     \
+    } while (0)
+    if (!g.a_t && !g.b_t) BP_GEMM_LAUNCH(false, true);        // forward: X k-major, W[K,N] r-major
+    else if (!g.a_t && g.b_t) BP_GEMM_LAUNCH(false, false);   // dgrad: dY k-major, W[n][k] k-major
+    else if (g.a_t && !g.b_t) BP_GEMM_LAUNCH(true, true);     // wgrad: X^T r-major, dY r-major
+    else BP_GEMM_LAUNCH(true, false);
+#undef BP_GEMM_LAUNCH
+    return hipGetLastError();
+}
+
+bool gemm_mfma_supported(const GemmArgs& g) {
+    auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+    if (g.K % 8 || g.lda % 8 || g.ldb % 8) return false;
+    if (!al16(g.A) || !al16(g.B)) return false;
+    // r-major operands are read in 8-element chunks along their row index
+    if (g.a_t && g.M % 8) return false;
+    if (!g.b_t && g.N % 8) return false;
+    return true;
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
+    const bool aligned128 = g.M % 128 == 0 && g.N % 128 == 0 && g.K % BK == 0;
+    if (!aligned128) return launch_cfg<128, 128, 2, 2, true>(g, s);
+    const bool aligned256 = g.M % 256 == 0 && g.N % 256 == 0;
+    const long t256 = (long)(g.M / 256) * (g.N / 256);
+    if (aligned256 && t256 >= 192) return launch_cfg<256, 256, 2, 2, false>(g, s);
+    return launch_cfg<128, 128, 2, 2, false>(g, s);
+}
+
+}  // namespace bp
