@@ -19,6 +19,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;
 
@@ -40,7 +41,7 @@ template <int R> constexpr int tile_bytes() { return R * BK * 2; }
 template <int R, int NT, bool RMAJOR, bool RAGGED>
 struct TileLoader {
     static constexpr int CH = R * 8 / NT;
-    uint4 regs[CH];
+    u32x4 regs[CH];
 
     // rows_valid: number of valid rows of this tile (M or N remainder); k_valid: valid k in slice
     __device__ __forceinline__ void load(const bf16_t* __restrict__ base, int ld, int rows_valid,
@@ -55,9 +56,10 @@ struct TileLoader {
             if (RAGGED) {
                 // chunks are 8 elements along the contiguous axis; shapes are multiples of 8 there
                 const bool ok = row < rows_valid && k < k_valid;
-                regs[i] = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                regs[i] = ok ? *reinterpret_cast<const u32x4*>(p) : zero;
             } else {
-                regs[i] = *reinterpret_cast<const uint4*>(p);
+                regs[i] = *reinterpret_cast<const u32x4*>(p);
             }
         }
     }
@@ -68,7 +70,7 @@ struct TileLoader {
             int off;
             if (RMAJOR) off = rmajor_off<R>(q / (R / 8), q % (R / 8));
             else off = kmajor_off(q >> 3, q & 7);
-            *reinterpret_cast<uint4*>(lds + off) = regs[i];
+            *reinterpret_cast<u32x4*>(lds + off) = regs[i];
         }
     }
 };
