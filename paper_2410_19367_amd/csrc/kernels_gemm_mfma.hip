@@ -213,6 +213,197 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(GemmArgs g, int 
     }
 }
 
+// =====================================================================================
+// Second kernel: aligned shapes.  Slices go global -> LDS directly (global_load_lds, 16 bytes per
+// lane, one wave instruction fills 1 KiB of consecutive LDS), so no registers or ds_write issue
+// slots are spent on staging; NS LDS stages let the loads run NS-1 slices ahead of the MFMAs.
+// Because the hardware fixes the LDS position of each lane's 16 bytes, the swizzled layouts
+// are produced by choosing which global chunk each lane fetches.
+// =====================================================================================
+
+template <int BKT> __device__ __forceinline__ int kmaj_swz(int row) {
+    return BKT == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+// byte offset of logical 16-byte chunk c of `row` in a k-major tile [R][BKT]
+template <int BKT> __device__ __forceinline__ int kmaj_off(int row, int c) {
+    return row * (BKT * 2) + ((c ^ kmaj_swz<BKT>(row)) << 4);
+}
+
+__device__ __forceinline__ void dma16(const void* gptr, char* lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
+                                     (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
+}
+
+// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+#define BP_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+// Per-lane element offsets (relative to the slice base) of the chunks this lane fetches.
+template <int R, int BKT, int NW, bool RMAJOR>
+struct DmaPlan {
+    static constexpr int NI = R * BKT / 512 / NW;   // wave instructions per wave per slice
+    int goff[NI];                                   // element offset from the slice base
+    __device__ __forceinline__ void init(int wave, int lane, int ld) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int P = (wave + NW * i) * 64 + lane;          // 16-byte position in the tile
+            if (RMAJOR) {
+                const int krow = P / (R / 8), p = P % (R / 8);
+                goff[i] = krow * ld + ((p ^ ((krow & 3) << 2)) << 3);
+            } else {
+                const int row = P / (BKT / 8), p = P % (BKT / 8);
+                goff[i] = row * ld + ((p ^ kmaj_swz<BKT>(row)) << 3);
+            }
+        }
+    }
+    __device__ __forceinline__ void issue(const bf16_t* slice_base, char* lds_tile, int wave) const {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) dma16(slice_base + goff[i], lds_tile + (wave + NW * i) * 1024);
+    }
+};
+
+template <int R, int BKT, bool RMAJOR>
+__device__ __forceinline__ bf16x8 read_frag2(const char* lds, int row0, int kk, int lane) {
+    const int h = lane >> 5;
+    if (!RMAJOR) {
+        return *reinterpret_cast<const bf16x8*>(lds + kmaj_off<BKT>(row0 + (lane & 31), kk * 2 + h));
+    } else {
+        const int i = lane & 15, g2 = (lane >> 4) & 1;
+        const int r = i >> 2, q = i & 3;
+        const int col = row0 + 16 * g2 + 4 * q;
+        const int chunk = col >> 3, byte = (col & 7) * 2;
+        const int k0 = kk * 16 + 8 * h;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(lds + rmajor_off<R>(k0 + r, chunk) + byte));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(lds + rmajor_off<R>(k0 + 4 + r, chunk) + byte));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, v);
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+    constexpr int NW = WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2, STAGE = A_BYTES + B_BYTES;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    // tile order: each XCD (blocks are dealt round-robin over 8 XCDs) gets a contiguous range of
+    // ids, walked in groups of 4 tile rows so that concurrent blocks share A rows and B columns
+    const int nblk = tiles_m * tiles_n;
+    int t = blockIdx.x;
+    if (nblk % 8 == 0) t = (t & 7) * (nblk >> 3) + (t >> 3);
+    constexpr int GM = 4;
+    const int per_group = GM * tiles_n;
+    const int first_m = (t / per_group) * GM;
+    const int gsize = min(tiles_m - first_m, GM);
+    const int tm = first_m + (t % per_group) % gsize, tn = (t % per_group) / gsize;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction
+    const int wm = wave / WN, wn = wave % WN;
+
+    const bf16_t* a_base = A_RMAJOR ? (const bf16_t*)g.A + m0 : (const bf16_t*)g.A + (size_t)m0 * g.lda;
+    const bf16_t* b_base = B_RMAJOR ? (const bf16_t*)g.B + n0 : (const bf16_t*)g.B + (size_t)n0 * g.ldb;
+    const size_t a_step = A_RMAJOR ? (size_t)BKT * g.lda : BKT;
+    const size_t b_step = B_RMAJOR ? (size_t)BKT * g.ldb : BKT;
+
+    DmaPlan<BM, BKT, NW, A_RMAJOR> pa;
+    DmaPlan<BN, BKT, NW, B_RMAJOR> pb;
+    pa.init(wave, lane, g.lda);
+    pb.init(wave, lane, g.ldb);
+    constexpr int LPT = decltype(pa)::NI + decltype(pb)::NI;   // loads per slice per wave
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = g.K / BKT;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) {
+        if (s < nk) {
+            pa.issue(a_base + s * a_step, smem + s * STAGE, wave);
+            pb.issue(b_base + s * b_step, smem + s * STAGE + A_BYTES, wave);
+        }
+    }
+
+    for (int kt = 0; kt < nk; ++kt) {
+        // slice kt has landed once at most (NS-2) later slices are still in flight
+        if (kt + NS - 2 < nk) { BP_WAIT_VMCNT((NS - 2) * LPT); } else { BP_WAIT_VMCNT(0); }
+        // the barrier publishes slice kt and retires every read of slice kt-1, whose stage the
+        // next loads overwrite
+        __syncthreads();
+        if (kt + NS - 1 < nk) {
+            char* st = smem + ((kt + NS - 1) % NS) * STAGE;
+            pa.issue(a_base + (size_t)(kt + NS - 1) * a_step, st, wave);
+            pb.issue(b_base + (size_t)(kt + NS - 1) * b_step, st + A_BYTES, wave);
+        }
+        const char* sa = smem + (kt % NS) * STAGE;
+        const char* sb = sa + A_BYTES;
+        // fragments are fetched one k16 step ahead of the MFMAs that use them
+        constexpr int KK = BKT / 16;
+        bf16x8 fa[2][TM], fb[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[0][i] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 32, 0, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[0][j] = read_frag2<BN, BKT, B_RMAJOR>(sb, wn * (BN / WN) + j * 32, 0, lane);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const int cb = kk & 1, nb = cb ^ 1;
+            if (kk + 1 < KK) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    fa[nb][i] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 32, kk + 1, lane);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    fb[nb][j] = read_frag2<BN, BKT, B_RMAJOR>(sb, wn * (BN / WN) + j * 32, kk + 1, lane);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][i], fb[cb][j], acc[i][j], 0, 0, 0);
+            if (kk + 1 < KK) {
+                // issue order: one LDS read between MFMAs until the next step's reads are out
+                constexpr int NREAD = (TM * (A_RMAJOR ? 2 : 1) + TN * (B_RMAJOR ? 2 : 1));
+#pragma unroll
+                for (int r = 0; r < NREAD; ++r) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
+                }
+            }
+        }
+    }
+
+    const int col_l = lane & 31, row_l = 4 * (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * (BN / WN) + j * 32 + col_l;
+        const float bias = (!g.accumulate && g.bias) ? g.bias[n] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+                const size_t o = (size_t)m * g.ldc + n;
+                if (g.accumulate) {
+                    ((float*)g.C)[o] += acc[i][j][v];
+                } else {
+                    float r = acc[i][j][v] + bias;
+                    if (g.residual) r += (float)((const bf16_t*)g.residual)[o];
+                    ((bf16_t*)g.C)[o] = (bf16_t)r;
+                }
+            }
+        }
+    }
+}
+
 // ---- host-side selection
 template <int BM, int BN, int WM, int WN, bool RAGGED>
 static hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
@@ -239,6 +430,31 @@ static hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     return hipGetLastError();
 }
 
+template <int BM, int BN, int WM, int WN, int NS>
+static hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
+    const int tiles_m = g.M / BM, tiles_n = g.N / BN;
+    const dim3 grid(tiles_m * tiles_n), block(WM * WN * 64);
+    const size_t smem = (size_t)NS * (BM + BN) * 64 * 2;
+#define BP_GEMM_LAUNCH(AR, BR)                                                                   \
+    do {                                                                                         \
+        auto kern = gemm_dma_kernel<BM, BN, WM, WN, 64, NS, AR, BR>;                             \
+        static bool attr_set = false;   /* once per instantiation */                             \
+        if (smem > 64 * 1024 && !attr_set) {                                                     \
+            hipError_t e = hipFuncSetAttribute((const void*)kern,                                \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+            if (e != hipSuccess) return e;                                                       \
+            attr_set = true;                                                                     \
+        }                                                                                        \
+        hipLaunchKernelGGL(kern, grid, block, smem, s, g, tiles_m, tiles_n);                     \
+    } while (0)
+    if (!g.a_t && !g.b_t) BP_GEMM_LAUNCH(false, true);
+    else if (!g.a_t && g.b_t) BP_GEMM_LAUNCH(false, false);
+    else if (g.a_t && !g.b_t) BP_GEMM_LAUNCH(true, true);
+    else BP_GEMM_LAUNCH(true, false);
+#undef BP_GEMM_LAUNCH
+    return hipGetLastError();
+}
+
 bool gemm_mfma_supported(const GemmArgs& g) {
     auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
     if (g.K % 8 || g.lda % 8 || g.ldb % 8) return false;
@@ -252,10 +468,10 @@ bool gemm_mfma_supported(const GemmArgs& g) {
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     const bool aligned128 = g.M % 128 == 0 && g.N % 128 == 0 && g.K % BK == 0;
     if (!aligned128) return launch_cfg<128, 128, 2, 2, true>(g, s);
+    // 256 x 256 tiles (8 waves) once they fill at least three quarters of the 256 CUs
     const bool aligned256 = g.M % 256 == 0 && g.N % 256 == 0;
-    const long t256 = (long)(g.M / 256) * (g.N / 256);
-    if (aligned256 && t256 >= 192) return launch_cfg<256, 256, 2, 2, false>(g, s);
-    return launch_cfg<128, 128, 2, 2, false>(g, s);
+    if (aligned256 && (long)(g.M / 256) * (g.N / 256) >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s);
+    return launch_dma<128, 128, 2, 2, 2>(g, s);
 }
 
 }  // namespace bp
