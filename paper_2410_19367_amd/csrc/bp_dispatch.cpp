@@ -9,10 +9,12 @@ hipError_t launch_gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
 }
 
 hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t stream) {
+    if (dtype == BF16 && attn_mfma_supported(a)) return launch_attn_fwd_mfma(a, stream);
     return launch_attn_fwd_generic(dtype, a, stream);
 }
 
 hipError_t launch_attn_bwd(int dtype, const AttnArgs& a, hipStream_t stream) {
+    if (dtype == BF16 && attn_mfma_supported(a)) return launch_attn_bwd_mfma(a, stream);
     return launch_attn_bwd_generic(dtype, a, stream);
 }
 

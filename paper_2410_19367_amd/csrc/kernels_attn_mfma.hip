@@ -1,0 +1,522 @@
+// Fused attention on the gfx950 matrix cores (bf16 inputs, fp32 softmax and accumulation):
+// forward with online softmax, and the backward as two deterministic kernels (dQ; dK and dV).
+//
+// All three kernels stream [64 rows][D] tiles of the packed qkv / dctx tensors through LDS with
+// direct global->LDS loads and never materialise an S x S matrix.  Scores are produced
+// transposed where that keeps the softmax row of a query inside one lane:
+//   forward, dQ :  S^T[key][q] = K Q^T      lane <-> query, registers <-> keys
+//   dK, dV      :  S  [q][key] = Q K^T      lane <-> key,   registers <-> queries
+// In both cases the probabilities leave the MFMA accumulators as the B operand of the next
+// product (the contraction index is the accumulator's row index), so P never goes through LDS.
+// The accumulator rows a lane holds come in groups of four consecutive indices, which is exactly
+// what the LDS transpose read (ds_read_b64_tr_b16) returns, so the A operands of those second
+// products (V^T, K^T, dO^T, Q^T) are read straight from the row-major tiles.
+//
+// One swizzle serves plain 16-byte fragment reads and transpose reads of the same tile:
+// chunk c of row r is stored at c ^ f(r), f chosen so that 16 consecutive rows (plain reads) and
+// 4 consecutive rows x 64 bytes (transpose reads) both cover all banks.
+#include "bp_kernels.h"
+#include "bp_device.h"
+
+namespace bp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define BP_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- tile layout: [rows][D] bf16, 16-byte chunks XOR-swizzled by row
+template <int D> __device__ __forceinline__ int swz(int row) {
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3))
+                    : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+template <int D> __device__ __forceinline__ int tile_off(int row, int chunk) {
+    return row * (D * 2) + ((chunk ^ swz<D>(row)) << 4);
+}
+
+// Direct global->LDS copy of a [64][D] tile by NW waves.  gbase points at (row 0, col 0) of the
+// tile, ld is the row pitch in elements.  Rows >= rows_valid are fetched from row 0 instead
+// (their values are masked or discarded by the caller), which keeps every access in bounds.
+template <int D, int NW>
+__device__ __forceinline__ void dma_tile(const bf16_t* gbase, int ld, char* lds, int wave, int lane,
+                                         int rows_valid) {
+    constexpr int CPR = D / 8;              // chunks per row
+    constexpr int NI = 64 * CPR / 64 / NW;  // wave instructions per wave
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int j = wave + NW * i;
+        const int P = j * 64 + lane;
+        int row = P / CPR;
+        const int c = (P % CPR) ^ swz<D>(row);
+        if (row >= rows_valid) row = 0;
+        __builtin_amdgcn_global_load_lds(
+            (const void __attribute__((address_space(1)))*)(gbase + (size_t)row * ld + c * 8),
+            (void __attribute__((address_space(3)))*)(lds + j * 1024), 16, 0, 0);
+    }
+}
+template <int D, int NW> constexpr int dma_per_wave() { return 64 * (D / 8) / 64 / NW; }
+
+// plain fragment: 8 consecutive columns (k16 step s, half h) of row (row0 + lane%32)
+template <int D>
+__device__ __forceinline__ bf16x8 frag_rows(const char* lds, int row0, int s, int lane) {
+    return *reinterpret_cast<const bf16x8*>(lds + tile_off<D>(row0 + (lane & 31), 2 * s + (lane >> 5)));
+}
+// transposed fragment for a product whose contraction runs over the tile's rows: lane gets, for
+// column (col0 + lane%32), the rows {r0 + 4h .. +3} and {r0 + 8 + 4h .. +3} (h = lane/32): the
+// row order in which a 32x32 accumulator hands its 16 rows to the next MFMA.
+template <int D>
+__device__ __forceinline__ bf16x8 frag_cols(const char* lds, int r0, int col0, int lane) {
+    const int i = lane & 15, g2 = (lane >> 4) & 1, h = lane >> 5;
+    const int col = col0 + 16 * g2 + 4 * (i & 3);
+    const int chunk = col >> 3, byte = (col & 7) * 2;
+    const int ra = r0 + 4 * h + (i >> 2);
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(lds + tile_off<D>(ra, chunk) + byte));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(lds + tile_off<D>(ra + 8, chunk) + byte));
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// accumulator registers 8*half .. 8*half+7 of a 32x32 tile as a bf16 B operand
+__device__ __forceinline__ bf16x8 acc_to_b(const f32x16& a, int half) {
+    bf16x8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (bf16_t)a[8 * half + e];
+    return r;
+}
+
+// row index inside a 32-row accumulator tile held in register v by a lane of half h
+__device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
+
+// =====================================================================================
+// Forward.  Block = 4 waves x 32 queries; K/V tiles of 64 keys, two LDS stages.
+// =====================================================================================
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float scale) {
+    constexpr int NW = 4, KS = D / 16, DT = D / 32;
+    constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE;   // K then V
+    constexpr int LPT = 2 * dma_per_wave<D, NW>();
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane >> 5;
+    const int qblk = a.causal ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;   // heavy blocks first
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int H = a.heads * D, ld = 3 * H;
+    const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * D;
+    const bf16_t* kbase = qkv + H;
+    const bf16_t* vbase = qkv + 2 * H;
+    const int q_wave = qblk * 128 + wave * 32;
+    const int q_lane = q_wave + (lane & 31);
+    const int klen = a.causal ? a.S : (a.lens ? a.lens[b] : a.S);
+    const int kend = a.causal ? min(qblk * 128 + 128, a.S) : klen;     // keys [0, kend) matter
+    const int nt = (kend + 63) / 64;
+    const float c = scale * kLog2e;
+
+    // Q as the B operand of S^T = K Q^T: lane = query, 8 consecutive d per k16 step
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+        qf[s] = *reinterpret_cast<const bf16x8*>(qkv + (size_t)q_lane * ld + 16 * s + 8 * h);
+
+    f32x16 ot[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ot[t][v] = 0.f;
+    float m = -INFINITY, lsum = 0.f;
+
+    dma_tile<D, NW>(kbase, ld, smem, wave, lane, a.S);
+    dma_tile<D, NW>(vbase, ld, smem + TILE, wave, lane, a.S);
+
+    for (int t = 0; t < nt; ++t) {
+        const int k0 = t * 64;
+        BP_WAIT_VMCNT(0);
+        __syncthreads();
+        if (t + 1 < nt) {
+            char* st = smem + ((t + 1) & 1) * STAGE;
+            const int rows = a.S - (k0 + 64);
+            dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows);
+            dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows);
+        }
+        if (a.causal && k0 > q_wave + 31) continue;     // every key of this tile is masked for this wave
+        const char* sk = smem + (t & 1) * STAGE;
+        const char* sv = sk + TILE;
+
+        // S^T (64 keys x 32 queries)
+        f32x16 st2[2];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) st2[kt][v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                st2[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, kt * 32, s, lane), qf[s],
+                                                                  st2[kt], 0, 0, 0);
+        }
+        // scale to the log2 domain, mask, running max
+        const bool need_mask = (a.causal && k0 + 63 > q_wave) || (k0 + 64 > klen);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float sv_ = st2[kt][v] * c;
+                if (need_mask) {
+                    const int key = k0 + kt * 32 + acc_row(v, h);
+                    if ((a.causal && key > q_lane) || key >= klen) sv_ = -INFINITY;
+                }
+                st2[kt][v] = sv_;
+                mx = fmaxf(mx, sv_);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m, mx);
+        const float alpha = exp2f(m - m_new);
+        m = m_new;
+        float ps = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float p = exp2f(st2[kt][v] - m_new);
+                st2[kt][v] = p;
+                ps += p;
+            }
+        lsum = lsum * alpha + ps;
+#pragma unroll
+        for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ot[t2][v] *= alpha;
+        // O^T (D x 32 queries) += V^T P^T
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) {
+            const bf16x8 pb = acc_to_b(st2[s2 >> 1], s2 & 1);
+#pragma unroll
+            for (int t2 = 0; t2 < DT; ++t2)
+                ot[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<D>(sv, 16 * s2, t2 * 32, lane), pb,
+                                                                 ot[t2], 0, 0, 0);
+        }
+    }
+
+    const float l = lsum + __shfl_xor(lsum, 32, 64);
+    const float inv = 1.f / l;
+    bf16_t* out = (bf16_t*)a.ctx + ((size_t)b * a.S + q_lane) * H + head * D;
+#pragma unroll
+    for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            // registers 4g..4g+3 are four consecutive d
+            uint2 pk;
+            pk.x = pack_bf16x2(ot[t2][4 * g] * inv, ot[t2][4 * g + 1] * inv);
+            pk.y = pack_bf16x2(ot[t2][4 * g + 2] * inv, ot[t2][4 * g + 3] * inv);
+            *reinterpret_cast<uint2*>(out + t2 * 32 + 8 * g + 4 * h) = pk;
+        }
+    if (h == 0) a.lse[((size_t)b * a.heads + head) * a.S + q_lane] = (m + log2f(l)) * kLn2;
+}
+
+// =====================================================================================
+// Backward, part 1: delta[q] = sum_d dO[q][d] * O[q][d]   (one wave per row)
+// =====================================================================================
+__global__ __launch_bounds__(256) void attn_delta_kernel(AttnArgs a, int D) {
+    const int lane = threadIdx.x & 63;
+    const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);     // over B*S*heads
+    const size_t total = (size_t)a.B * a.S * a.heads;
+    if (row >= total) return;
+    const int head = (int)(row % a.heads);
+    const size_t tok = row / a.heads;
+    const int H = a.heads * D;
+    const bf16_t* o = (const bf16_t*)a.ctx + tok * H + head * D;
+    const bf16_t* d_o = (const bf16_t*)a.dctx + tok * H + head * D;
+    float s = 0.f;
+    for (int c = lane * 2; c < D; c += 128)
+        s += (float)o[c] * (float)d_o[c] + (float)o[c + 1] * (float)d_o[c + 1];
+    s = wave_sum(s);
+    if (lane == 0) {
+        const size_t bb = tok / a.S, ss = tok % a.S;
+        a.delta[(bb * a.heads + head) * a.S + ss] = s;
+    }
+}
+
+// =====================================================================================
+// Backward, part 2: dQ.  Same structure as the forward: lane <-> query.
+//   S^T = K Q^T, P^T = exp(S^T - lse), dP^T = V dO^T, dS^T = P^T (dP^T - delta),
+//   dQ^T (D x 32) += K^T dS^T         (K tile read plainly for S^T and transposed for dQ^T)
+// =====================================================================================
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, float scale) {
+    constexpr int NW = 4, KS = D / 16, DT = D / 32;
+    constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane >> 5;
+    const int qblk = a.causal ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int H = a.heads * D, ld = 3 * H;
+    const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * D;
+    const bf16_t* kbase = qkv + H;
+    const bf16_t* vbase = qkv + 2 * H;
+    const int q_wave = qblk * 128 + wave * 32;
+    const int q_lane = q_wave + (lane & 31);
+    const int klen = a.causal ? a.S : (a.lens ? a.lens[b] : a.S);
+    const int kend = a.causal ? min(qblk * 128 + 128, a.S) : klen;
+    const int nt = (kend + 63) / 64;
+    const float c = scale * kLog2e;
+
+    const bf16_t* dob = (const bf16_t*)a.dctx + ((size_t)b * a.S + q_lane) * H + head * D;
+    bf16x8 qf[KS], dof[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        qf[s] = *reinterpret_cast<const bf16x8*>(qkv + (size_t)q_lane * ld + 16 * s + 8 * h);
+        dof[s] = *reinterpret_cast<const bf16x8*>(dob + 16 * s + 8 * h);
+    }
+    const size_t li = ((size_t)b * a.heads + head) * a.S + q_lane;
+    const float lse2 = a.lse[li] * kLog2e;
+    const float delta = a.delta[li];
+
+    f32x16 dq[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dq[t][v] = 0.f;
+
+    dma_tile<D, NW>(kbase, ld, smem, wave, lane, a.S);
+    dma_tile<D, NW>(vbase, ld, smem + TILE, wave, lane, a.S);
+
+    for (int t = 0; t < nt; ++t) {
+        const int k0 = t * 64;
+        BP_WAIT_VMCNT(0);
+        __syncthreads();
+        if (t + 1 < nt) {
+            char* st = smem + ((t + 1) & 1) * STAGE;
+            const int rows = a.S - (k0 + 64);
+            dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows);
+            dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows);
+        }
+        if (a.causal && k0 > q_wave + 31) continue;
+        const char* sk = smem + (t & 1) * STAGE;
+        const char* sv = sk + TILE;
+        const bool need_mask = (a.causal && k0 + 63 > q_wave) || (k0 + 64 > klen);
+        f32x16 ds[2];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            f32x16 sacc, dp;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, kt * 32, s, lane), qf[s], sacc, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sv, kt * 32, s, lane), dof[s], dp, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float p = exp2f(sacc[v] * c - lse2);
+                if (need_mask) {
+                    const int key = k0 + kt * 32 + acc_row(v, h);
+                    if ((a.causal && key > q_lane) || key >= klen) p = 0.f;
+                }
+                ds[kt][v] = p * (dp[v] - delta);
+            }
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) {
+            const bf16x8 db = acc_to_b(ds[s2 >> 1], s2 & 1);
+#pragma unroll
+            for (int t2 = 0; t2 < DT; ++t2)
+                dq[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<D>(sk, 16 * s2, t2 * 32, lane), db,
+                                                                 dq[t2], 0, 0, 0);
+        }
+    }
+    bf16_t* out = (bf16_t*)a.dqkv + ((size_t)b * a.S + q_lane) * ld + head * D;
+#pragma unroll
+    for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint2 pk;
+            pk.x = pack_bf16x2(dq[t2][4 * g] * scale, dq[t2][4 * g + 1] * scale);
+            pk.y = pack_bf16x2(dq[t2][4 * g + 2] * scale, dq[t2][4 * g + 3] * scale);
+            *reinterpret_cast<uint2*>(out + t2 * 32 + 8 * g + 4 * h) = pk;
+        }
+}
+
+// =====================================================================================
+// Backward, part 3: dK and dV.  Block = 4 waves x 32 keys; Q/dO tiles of 64 queries stream by.
+//   S = Q K^T (lane <-> key), P = exp(S - lse[q]), dP = dO V^T, dS = P (dP - delta[q]),
+//   dV^T (D x 32 keys) += dO^T P,   dK^T (D x 32 keys) += Q^T dS
+// =====================================================================================
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, float scale) {
+    constexpr int NW = 4, KS = D / 16, DT = D / 32;
+    constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE + 512;   // Q, dO, then lse[64], delta[64]
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane >> 5;
+    const int kblk = blockIdx.x;
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int H = a.heads * D, ld = 3 * H;
+    const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * D;
+    const bf16_t* dobase = (const bf16_t*)a.dctx + (size_t)b * a.S * H + head * D;
+    const int k_wave = kblk * 128 + wave * 32;
+    const int k_lane = k_wave + (lane & 31);
+    const int klen = a.causal ? a.S : (a.lens ? a.lens[b] : a.S);
+    bf16_t* dk_out = (bf16_t*)a.dqkv + ((size_t)b * a.S + k_lane) * ld + H + head * D;
+    bf16_t* dv_out = dk_out + H;
+    if (kblk * 128 >= klen) {      // the whole block of keys is padding: no query attends it
+        const uint2 z = make_uint2(0u, 0u);
+#pragma unroll
+        for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                *reinterpret_cast<uint2*>(dk_out + t2 * 32 + 8 * g + 4 * h) = z;
+                *reinterpret_cast<uint2*>(dv_out + t2 * 32 + 8 * g + 4 * h) = z;
+            }
+        return;
+    }
+    const float c = scale * kLog2e;
+    const float* lse = a.lse + ((size_t)b * a.heads + head) * a.S;
+    const float* dlt = a.delta + ((size_t)b * a.heads + head) * a.S;
+
+    // K and V of this lane's key as B operands (lane = key column, 8 consecutive d per step)
+    bf16x8 kf[KS], vf[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        kf[s] = *reinterpret_cast<const bf16x8*>(qkv + H + (size_t)k_lane * ld + 16 * s + 8 * h);
+        vf[s] = *reinterpret_cast<const bf16x8*>(qkv + 2 * H + (size_t)k_lane * ld + 16 * s + 8 * h);
+    }
+    f32x16 dk[DT], dv[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { dk[t][v] = 0.f; dv[t][v] = 0.f; }
+
+    // queries that can attend this block's keys: causal -> q >= first key of the block
+    const int t0 = a.causal ? (kblk * 128) / 64 : 0;
+    const int nt = a.S / 64;
+
+    auto load_stage = [&](int t, char* st) {
+        const int q0 = t * 64;
+        dma_tile<D, NW>(qkv + (size_t)q0 * ld, ld, st, wave, lane, a.S - q0);
+        dma_tile<D, NW>(dobase + (size_t)q0 * H, H, st + TILE, wave, lane, a.S - q0);
+        if (threadIdx.x < 64) ((float*)(st + 2 * TILE))[threadIdx.x] = lse[q0 + threadIdx.x] * kLog2e;
+        else if (threadIdx.x < 128) ((float*)(st + 2 * TILE))[threadIdx.x] = dlt[q0 + threadIdx.x - 64];
+    };
+    load_stage(t0, smem + (t0 & 1) * STAGE);
+
+    for (int t = t0; t < nt; ++t) {
+        const int q0 = t * 64;
+        BP_WAIT_VMCNT(0);
+        __syncthreads();
+        if (t + 1 < nt) load_stage(t + 1, smem + ((t + 1) & 1) * STAGE);
+        if (a.causal && q0 + 63 < k_wave) continue;      // no query of this tile reaches this wave's keys
+        const char* sq = smem + (t & 1) * STAGE;
+        const char* sdo = sq + TILE;
+        const float* s_lse = (const float*)(sq + 2 * TILE);
+        const float* s_dlt = s_lse + 64;
+        const bool need_mask = a.causal && q0 < k_wave + 31;
+        f32x16 pacc[2], ds[2];
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            f32x16 sacc, dp;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sq, qt * 32, s, lane), kf[s], sacc, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sdo, qt * 32, s, lane), vf[s], dp, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int qi = qt * 32 + acc_row(v, h);
+                float p = exp2f(sacc[v] * c - s_lse[qi]);
+                if (need_mask && k_lane > q0 + qi) p = 0.f;
+                if (k_lane >= klen) p = 0.f;
+                pacc[qt][v] = p;
+                ds[qt][v] = p * (dp[v] - s_dlt[qi]);
+            }
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) {
+            const bf16x8 pb = acc_to_b(pacc[s2 >> 1], s2 & 1);
+            const bf16x8 db = acc_to_b(ds[s2 >> 1], s2 & 1);
+#pragma unroll
+            for (int t2 = 0; t2 < DT; ++t2) {
+                dv[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<D>(sdo, 16 * s2, t2 * 32, lane), pb, dv[t2], 0, 0, 0);
+                dk[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<D>(sq, 16 * s2, t2 * 32, lane), db, dk[t2], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint2 pk;
+            pk.x = pack_bf16x2(dk[t2][4 * g] * scale, dk[t2][4 * g + 1] * scale);
+            pk.y = pack_bf16x2(dk[t2][4 * g + 2] * scale, dk[t2][4 * g + 3] * scale);
+            *reinterpret_cast<uint2*>(dk_out + t2 * 32 + 8 * g + 4 * h) = pk;
+            pk.x = pack_bf16x2(dv[t2][4 * g], dv[t2][4 * g + 1]);
+            pk.y = pack_bf16x2(dv[t2][4 * g + 2], dv[t2][4 * g + 3]);
+            *reinterpret_cast<uint2*>(dv_out + t2 * 32 + 8 * g + 4 * h) = pk;
+        }
+}
+
+// ---- host side
+bool attn_mfma_supported(const AttnArgs& a) {
+    auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+    if (a.d != 64 && a.d != 128) return false;
+    if (a.S % 128) return false;
+    return al16(a.qkv) && al16(a.ctx) && (!a.dctx || al16(a.dctx)) && (!a.dqkv || al16(a.dqkv));
+}
+
+template <typename K>
+static hipError_t set_smem(K kern, size_t smem) {
+    if (smem <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+}
+
+hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
+    const float scale = 1.f / sqrtf((float)a.d);
+    const dim3 grid(a.S / 128, a.heads, a.B), block(256);
+    if (a.d == 128) {
+        const size_t smem = 2 * 2 * 64 * 128 * 2;
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<128>), grid, block, smem, s, a, scale);
+    } else {
+        const size_t smem = 2 * 2 * 64 * 64 * 2;
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<64>), grid, block, smem, s, a, scale);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
+    const float scale = 1.f / sqrtf((float)a.d);
+    const size_t rows = (size_t)a.B * a.S * a.heads;
+    hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a, a.d);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 grid(a.S / 128, a.heads, a.B), block(256);
+    if (a.d == 128) {
+        const size_t smem = 2 * 2 * 64 * 128 * 2, smem2 = 2 * (2 * 64 * 128 * 2 + 512);
+        static bool set = false;
+        if (!set) {
+            if ((e = set_smem(attn_bwd_dkv_mfma_kernel<128>, smem2)) != hipSuccess) return e;
+            set = true;
+        }
+        hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<128>), grid, block, smem, s, a, scale);
+        hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<128>), grid, block, smem2, s, a, scale);
+    } else {
+        const size_t smem = 2 * 2 * 64 * 64 * 2, smem2 = 2 * (2 * 64 * 64 * 2 + 512);
+        hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<64>), grid, block, smem, s, a, scale);
+        hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<64>), grid, block, smem2, s, a, scale);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace bp

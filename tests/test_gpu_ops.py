@@ -141,6 +141,10 @@ ATTN_CASES = [
     (2, 256, 2, 128, False, [256, 130]),
     (2, 96, 2, 64, False, None),
     (1, 72, 1, 32, True, None),
+    (3, 128, 2, 64, False, [128, 41, 97]),
+    (2, 256, 2, 64, False, None),
+    (1, 640, 2, 128, False, [333]),
+    (2, 1024, 1, 128, True, None),
 ]
 
 
