@@ -352,7 +352,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
 //   dV^T (D x 32 keys) += dO^T P,   dK^T (D x 32 keys) += Q^T dS
 // =====================================================================================
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, float scale) {
+__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, float scale) {
     constexpr int NW = 4, KS = D / 16, DT = D / 32;
     constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE + 512;   // Q, dO, then lse[64], delta[64]
     extern __shared__ __attribute__((aligned(16))) char smem[];

@@ -131,18 +131,29 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
     const int r1 = min(r0 + kColsumRows, rows);
     float sa[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (col < N) {
-        for (int r = r0 + w; r < r1; r += 4) {
-            float a[8];
-            load8(A + (size_t)r * N + col, a);
-            if (WITH_X) {
-                float xv[8];
-                load8(X + (size_t)r * N + col, xv);
-                const float mu = mean[r], rs = rstd[r];
+        // all of this wave's rows are requested before the first one is consumed
+        constexpr int RPW = kColsumRows / 4;
+        float a[RPW][8], xv[RPW][8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) sx[i] += a[i] * (xv[i] - mu) * rs;
+        for (int j = 0; j < RPW; ++j) {
+            const int r = r0 + w + 4 * j;
+            if (r < r1) {
+                load8(A + (size_t)r * N + col, a[j]);
+                if (WITH_X) load8(X + (size_t)r * N + col, xv[j]);
             }
+        }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) sa[i] += a[i];
+        for (int j = 0; j < RPW; ++j) {
+            const int r = r0 + w + 4 * j;
+            if (r < r1) {
+                if (WITH_X) {
+                    const float mu = mean[r], rs = rstd[r];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) sx[i] += a[j][i] * (xv[j][i] - mu) * rs;
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) sa[i] += a[j][i];
+            }
         }
     }
 #pragma unroll
@@ -219,21 +230,32 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* dg,   // may ali
     if (col < F) {
         float b[8];
         load8(bias + col, b);
-        for (int r = r0 + w; r < r1; r += 4) {
-            float a[8], d[8], o[8];
-            load8(u + (size_t)r * F + col, a);
-            load8(dg + (size_t)r * F + col, d);
+        constexpr int RPW = kColsumRows / 4;
+        float a[RPW][8], d[RPW][8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float x = a[i] + b[i];
-                const float t = gelu_tanh_part(x);
-                const float dudx = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
-                const float gp = 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * dudx;
-                o[i] = d[i] * gp;
+        for (int j = 0; j < RPW; ++j) {
+            const int r = r0 + w + 4 * j;
+            if (r < r1) {
+                load8(u + (size_t)r * F + col, a[j]);
+                load8(dg + (size_t)r * F + col, d[j]);
             }
-            store8(du + (size_t)r * F + col, o);
+        }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] += o[i];
+        for (int j = 0; j < RPW; ++j) {
+            const int r = r0 + w + 4 * j;
+            if (r < r1) {
+                float o[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float x = a[j][i] + b[i];
+                    const float t = gelu_tanh_part(x);
+                    const float dudx = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
+                    const float gp = 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * dudx;
+                    o[i] = d[j][i] * gp;
+                    acc[i] += o[i];
+                }
+                store8(du + (size_t)r * F + col, o);
+            }
         }
     }
 #pragma unroll
