@@ -38,6 +38,8 @@ struct StashSlot {
     void* buf = nullptr;   // L * s_layer_bytes, allocated on first use and kept
     bool live = false;
     int chunk = -1, mb = -1;
+    hipEvent_t side_done = nullptr;   // last side-stream reader of this slot (null: none pending)
+    bool side_pending = false;
 };
 
 struct Stage {
@@ -48,6 +50,15 @@ struct Stage {
     size_t esz = 2;
     float eps = 1e-5f;
     hipStream_t stream = nullptr;
+    // Weight-gradient GEMMs and the column reductions of the backward run on a second stream so
+    // that their memory-bound tails overlap the next data-gradient kernels; events order the two.
+    hipStream_t side = nullptr;
+    bool overlap = true;                 // false: everything on `stream` (also while timing kernels)
+    hipEvent_t ev_ready[5] = {};         // main -> side: dz, du, dy, dqkv, da of the current layer
+    hipEvent_t ev_layer_done[2] = {};    // side -> main: workspaces of layer parity p are free again
+    bool layer_done_pending[2] = {false, false};
+    hipEvent_t ev_misc = nullptr;        // side -> main: end of the previous backward call
+    bool call_done_pending = false;
 
     // parameters (matrices in the storage dtype, vectors fp32) and fp32 gradients per direction
     void* params = nullptr;
@@ -60,8 +71,11 @@ struct Stage {
     std::vector<StashSlot> slots;
 
     // backward workspaces
-    void *ws_big1 = nullptr, *ws_big2 = nullptr, *ws_h1 = nullptr, *ws_h2 = nullptr, *ws_h3 = nullptr;
-    float *ws_delta = nullptr, *ws_colsum = nullptr;
+    // backward workspaces; those the side stream reads exist once per layer parity, dx rotates
+    // over three buffers (layer l writes l % 3, layer l-1 and its side work read it)
+    void *ws_big1[2] = {}, *ws_big2[2] = {}, *ws_h1[2] = {}, *ws_h2[2] = {}, *ws_h5[2] = {};
+    void *ws_h4 = nullptr, *ws_dx[3] = {};
+    float *ws_delta = nullptr, *ws_colsum[2] = {};
 
     // key-padding lengths per micro-batch (device int32 [B])
     std::map<int, int32_t*> lens;
@@ -95,7 +109,10 @@ struct Stage {
     int live_slots() const;
 
     int gemm(const void* A, int lda, int a_t, const void* Bm, int ldb, int b_t, void* C, int ldc,
-             int M, int N, int K, const float* bias, const void* residual, int accumulate);
+             int M, int N, int K, const float* bias, const void* residual, int accumulate,
+             hipStream_t on = nullptr, bool use_on = false);
+    hipStream_t side_stream() const { return (overlap && !prof.on && side) ? side : stream; }
+    int sync_all();
     int forward(int chunk, int mb, const void* act_in, void* act_out);
     int backward(int chunk, int mb, const void* grad_out, void* grad_in, int dir);
     int run_schedule(const bp_op* order, int n_ops, int D, const void* inputs, const void* targets,

@@ -47,6 +47,25 @@ hipError_t launch_ln_bwd_rows(int dtype, int T, int H, const void* dout, const v
 //   out_a[c]  += sum_t A[t,c]
 //   out_ax[c] += sum_t A[t,c] * (X[t,c]-mean[t])*rstd[t]     (only when X != null)
 // ws: colsum_chunks(T) * N * (X ? 2 : 1) floats.
+// A batch of column reductions over tensors with the same number of rows.  A job with A == null
+// only folds partials that another kernel already left in `part` (chunk-major [chunks][N]).
+struct ColsumJob {
+    const void* A;        // [T,N] storage dtype, or null
+    const void* X;        // [T,N] or null; with X: out_ax += sum_t A * (X - mean) * rstd
+    const float* mean;
+    const float* rstd;
+    int N;
+    float* out_a;         // += sum_t A
+    float* out_ax;        // or null
+    float* part;          // colsum_chunks(T) * N * (out_ax ? 2 : 1) floats
+};
+constexpr int kMaxColsumJobs = 8;
+struct ColsumBatch {
+    ColsumJob jobs[kMaxColsumJobs];
+    int n;
+};
+hipError_t launch_colsum_batch(int dtype, int T, const ColsumBatch& batch, hipStream_t stream);
+
 hipError_t launch_colsum(int dtype, int T, int N, const void* A, const void* X,
                          const float* mean, const float* rstd, float* out_a, float* out_ax,
                          float* ws, hipStream_t stream);

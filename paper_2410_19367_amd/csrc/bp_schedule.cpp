@@ -234,12 +234,12 @@ int Stage::run_schedule(const bp_op* order, int n_ops, int D, const void* inputs
 
     const size_t TH = (size_t)T * H, THb = TH * esz;
     if (sched_n < N) {
-        hipStreamSynchronize(stream);
+        sync_all();
         hipFree(sched_act); hipFree(sched_grad); hipFree(sched_loss);
         sched_act = sched_grad = nullptr; sched_loss = nullptr; sched_n = 0;
         if (hipMalloc(&sched_act, (size_t)N * 2 * THb) != hipSuccess ||
             hipMalloc(&sched_grad, (size_t)N * THb) != hipSuccess ||
-            hipMalloc((void**)&sched_loss, (size_t)N * sizeof(float)) != hipSuccess) {
+            hipMalloc((void**)&sched_loss, ((size_t)N + 1024) * sizeof(float)) != hipSuccess) {
             (void)hipGetLastError();
             return fail(BP_ENOMEM, "allocating the iteration's hand-off buffers failed");
         }
@@ -265,7 +265,7 @@ int Stage::run_schedule(const bp_op* order, int n_ops, int D, const void* inputs
             if (o.stage == last) {
                 struct Guard { Stage* s; Guard(Stage* st) : s(st) { s->prof.begin(s, BP_K_OTHER, 0, 0); } ~Guard() { s->prof.end(s); } } g(this);
                 hipError_t e = launch_loss(dtype, TH, out, (const char*)targets + (size_t)o.mb * THb, scale,
-                                           mb_grad, sched_loss + o.mb, ws_colsum, stream);
+                                           mb_grad, sched_loss + o.mb, sched_loss + sched_n, stream);   // partials after the N losses
                 if (e != hipSuccess) return fail(BP_EHIP, "loss kernel: %s", hipGetErrorString(e));
             }
         } else {
@@ -277,6 +277,7 @@ int Stage::run_schedule(const bp_op* order, int n_ops, int D, const void* inputs
     hipError_t e = hipMemcpyAsync(host_loss.data(), sched_loss, N * sizeof(float), hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail(BP_EHIP, "end of iteration: %s", hipGetErrorString(e));
+    if ((rc = sync_all())) return rc;
     if (loss_out) {
         double s = 0.0;
         for (int m = 0; m < N; ++m) s += host_loss[m];

@@ -173,15 +173,31 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
 
     // backward workspaces
     const size_t big = std::max((size_t)st->F, (size_t)3 * st->H);
-    if ((rc = dev_alloc(&st->ws_big1, (size_t)st->T * big * st->esz)) ||
-        (rc = dev_alloc(&st->ws_big2, (size_t)st->T * 3 * st->H * st->esz)) ||
-        (rc = dev_alloc(&st->ws_h1, TH)) || (rc = dev_alloc(&st->ws_h2, TH)) ||
-        (rc = dev_alloc(&st->ws_h3, TH)) ||
-        (rc = dev_alloc((void**)&st->ws_delta, (size_t)st->B * st->heads * st->S * sizeof(float))) ||
-        (rc = dev_alloc((void**)&st->ws_colsum,
-                        std::max<size_t>(2 * colsum_chunks(st->T) * big, 1024) * sizeof(float)))) {
-        delete st;
-        return rc;
+    rc = BP_OK;
+    for (int p = 0; p < 2 && !rc; ++p) {
+        (rc = dev_alloc(&st->ws_big1[p], (size_t)st->T * big * st->esz)) ||
+            (rc = dev_alloc(&st->ws_big2[p], (size_t)st->T * 3 * st->H * st->esz)) ||
+            (rc = dev_alloc(&st->ws_h1[p], TH)) || (rc = dev_alloc(&st->ws_h2[p], TH)) ||
+            (rc = dev_alloc(&st->ws_h5[p], TH)) ||
+            (rc = dev_alloc((void**)&st->ws_colsum[p],
+                            std::max<size_t>(colsum_chunks(st->T) * ((size_t)9 * st->H + st->F), 1024) *
+                                sizeof(float)));
+    }
+    for (int i = 0; i < 3 && !rc; ++i) rc = dev_alloc(&st->ws_dx[i], TH);
+    if (!rc) rc = dev_alloc(&st->ws_h4, TH);
+    if (!rc) rc = dev_alloc((void**)&st->ws_delta, (size_t)st->B * st->heads * st->S * sizeof(float));
+    if (rc) { delete st; return rc; }
+
+    // second stream (default priority, not synchronising with the null stream) and its events
+    {
+        hipError_t e = hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking);
+        for (int i = 0; i < 5 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&st->ev_ready[i], hipEventDisableTiming);
+        for (int i = 0; i < 2 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&st->ev_layer_done[i], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&st->ev_misc, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            delete st;
+            return fail(BP_EHIP, "creating the side stream failed: %s", hipGetErrorString(e));
+        }
     }
 
     // initial values: zeros, LN gamma = 1
@@ -202,14 +218,30 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     return BP_OK;
 }
 
+int Stage::sync_all() {
+    hipError_t e = hipStreamSynchronize(stream);
+    if (e == hipSuccess && side) e = hipStreamSynchronize(side);
+    if (e != hipSuccess) return fail(BP_EHIP, "synchronise: %s", hipGetErrorString(e));
+    return BP_OK;
+}
+
 Stage::~Stage() {
-    if (stream_valid()) hipStreamSynchronize(stream);
+    hipStreamSynchronize(stream);
+    if (side) { hipStreamSynchronize(side); hipStreamDestroy(side); }
+    for (auto e : ev_ready) if (e) hipEventDestroy(e);
+    for (auto e : ev_layer_done) if (e) hipEventDestroy(e);
+    if (ev_misc) hipEventDestroy(ev_misc);
     hipFree(params);
     hipFree(grads[0]);
     hipFree(grads[1]);
-    for (auto& s : slots) hipFree(s.buf);
-    hipFree(ws_big1); hipFree(ws_big2); hipFree(ws_h1); hipFree(ws_h2); hipFree(ws_h3);
-    hipFree(ws_delta); hipFree(ws_colsum);
+    for (auto& s : slots) { hipFree(s.buf); if (s.side_done) hipEventDestroy(s.side_done); }
+    for (int p = 0; p < 2; ++p) {
+        hipFree(ws_big1[p]); hipFree(ws_big2[p]); hipFree(ws_h1[p]); hipFree(ws_h2[p]); hipFree(ws_h5[p]);
+        hipFree(ws_colsum[p]);
+    }
+    for (auto b : ws_dx) hipFree(b);
+    hipFree(ws_h4);
+    hipFree(ws_delta);
     for (auto& kv : lens) hipFree(kv.second);
     hipFree(sched_act); hipFree(sched_grad); hipFree(sched_loss);
 }
@@ -257,6 +289,7 @@ int Stage::get_grad(int chunk, int layer, int id, float* host, size_t n) {
     int rc = check_tensor(chunk, layer, id, n);
     if (rc) return rc;
     if (!host) return fail(BP_EINVAL, "host pointer is null");
+    if ((rc = sync_all())) return rc;
     hipError_t e = hipMemcpyAsync(host, grad(0, chunk, layer, id), n * sizeof(float),
                                   hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
@@ -267,8 +300,10 @@ int Stage::get_grad(int chunk, int layer, int id, float* host, size_t n) {
 int Stage::zero_grad() {
     const size_t n = (size_t)n_chunks * L * g_layer_bytes / sizeof(float);
     Scoped sc(this, BP_K_OTHER, 0, 0);
-    hipError_t e = launch_fill_f32(grads[0], n, 0.f, stream);
-    if (e == hipSuccess) e = launch_fill_f32(grads[1], n, 0.f, stream);
+    // every writer of the gradient buffers runs on the side stream, so the clear goes there too
+    hipStream_t gs = side_stream();
+    hipError_t e = launch_fill_f32(grads[0], n, 0.f, gs);
+    if (e == hipSuccess) e = launch_fill_f32(grads[1], n, 0.f, gs);
     if (e != hipSuccess) return fail(BP_EHIP, "zero_grad: %s", hipGetErrorString(e));
     return BP_OK;
 }
@@ -276,8 +311,9 @@ int Stage::zero_grad() {
 int Stage::merge_directions() {
     const size_t n = (size_t)n_chunks * L * g_layer_bytes / sizeof(float);
     Scoped sc(this, BP_K_OTHER, 0, 0);
-    hipError_t e = launch_add_f32(grads[0], grads[1], n, stream);
-    if (e == hipSuccess) e = launch_fill_f32(grads[1], n, 0.f, stream);
+    hipStream_t gs = side_stream();
+    hipError_t e = launch_add_f32(grads[0], grads[1], n, gs);
+    if (e == hipSuccess) e = launch_fill_f32(grads[1], n, 0.f, gs);
     if (e != hipSuccess) return fail(BP_EHIP, "merge_directions: %s", hipGetErrorString(e));
     return BP_OK;
 }
@@ -328,6 +364,12 @@ int Stage::acquire_slot(int chunk, int mb, int* out) {
             int rc = dev_alloc(&slots[i].buf, (size_t)L * s_layer_bytes);
             if (rc) return rc;
         }
+        if (slots[i].side_pending) {
+            // the previous owner's weight-gradient kernels may still be reading this stash
+            hipError_t e = hipStreamWaitEvent(stream, slots[i].side_done, 0);
+            if (e != hipSuccess) return fail(BP_EHIP, "stash reuse wait: %s", hipGetErrorString(e));
+            slots[i].side_pending = false;
+        }
         slots[i].live = true; slots[i].chunk = chunk; slots[i].mb = mb;
         *out = (int)i;
         return BP_OK;
@@ -344,13 +386,14 @@ int Stage::acquire_slot(int chunk, int mb, int* out) {
     } while (0)
 
 int Stage::gemm(const void* A, int lda, int a_t, const void* Bm, int ldb, int b_t, void* C, int ldc,
-                int M, int N, int K, const float* bias, const void* residual, int accumulate) {
+                int M, int N, int K, const float* bias, const void* residual, int accumulate,
+                hipStream_t on, bool use_on) {
     GemmArgs g;
     g.A = A; g.B = Bm; g.C = C; g.bias = bias; g.residual = residual;
     g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
     g.a_t = a_t; g.b_t = b_t; g.accumulate = accumulate;
     Scoped sc(this, BP_K_GEMM, 2.0 * M * N * K, 0);
-    BP_LAUNCH(launch_gemm(dtype, g, stream));
+    BP_LAUNCH(launch_gemm(dtype, g, use_on ? on : stream));
     return BP_OK;
 }
 
@@ -420,62 +463,130 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
     const double attn_c = causal ? 0.5 : 1.0;
     int rc;
 
+    // Main stream: the chain of data gradients.  Side stream: weight gradients and column sums,
+    // each waiting for the main-stream kernel that produced its input.
+    hipStream_t ss = side_stream();
+    const bool two = ss != stream;
+#define BP_HIP(expr)                                                                    \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess) return fail(BP_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+    auto hand_over = [&](int k) -> hipError_t {    // side waits for what main has enqueued so far
+        if (!two) return hipSuccess;
+        hipError_t e = hipEventRecord(ev_ready[k], stream);
+        return e != hipSuccess ? e : hipStreamWaitEvent(ss, ev_ready[k], 0);
+    };
+
+    if (two && call_done_pending) {
+        // the workspaces are shared by all calls: the previous backward's side work must be over
+        BP_HIP(hipStreamWaitEvent(stream, ev_misc, 0));
+        call_done_pending = false;
+        layer_done_pending[0] = layer_done_pending[1] = false;
+    }
+
     const void* dz = grad_out;
     for (int l = L - 1; l >= 0; --l) {
+        const int p = l & 1;
         char* sb = (char*)slots[slot].buf + (size_t)l * s_layer_bytes;
         auto P = [&](int id) { return param(chunk, l, id); };
         auto G = [&](int id) { return grad(dir, chunk, l, id); };
-        void* dx = l == 0 ? grad_in : ws_h3;
-        // z = y + g W2 + b2
-        if ((rc = gemm(dz, H, 0, P(BP_W2), H, 1, ws_big1, F, T, F, H, nullptr, nullptr, 0))) return rc;   // dg
-        if ((rc = gemm(sb + s_g, F, 1, dz, H, 0, G(BP_W2), H, F, H, T, nullptr, nullptr, 1))) return rc;   // dW2
-        {   // du = dg * gelu'(u + b1), db1
-            Scoped sc(this, BP_K_GELU_BWD, 0, 3.0 * T * F * esz);
-            BP_LAUNCH(launch_gelu_bwd(dtype, T, F, ws_big1, sb + s_u, (const float*)P(BP_B1), ws_big1,
-                                      G(BP_B1), ws_colsum, stream));
+        void* dx = l == 0 ? grad_in : ws_dx[l % 3];
+        void *big1 = ws_big1[p], *big2 = ws_big2[p], *h1 = ws_h1[p], *h2 = ws_h2[p], *h5 = ws_h5[p];
+        if (two && layer_done_pending[p]) {     // workspaces of this parity still read by the side stream?
+            BP_HIP(hipStreamWaitEvent(stream, ev_layer_done[p], 0));
+            layer_done_pending[p] = false;
         }
-        if ((rc = gemm(ws_big1, F, 0, P(BP_W1), F, 1, ws_h1, H, T, H, F, nullptr, nullptr, 0))) return rc;   // dm
-        if ((rc = gemm(sb + s_m, H, 1, ws_big1, F, 0, G(BP_W1), F, H, F, T, nullptr, nullptr, 1))) return rc; // dW1
+        // column-sum partial regions: db2 | (dgamma2, dbeta2) | dbo | dbqkv | (dgamma1, dbeta1) | db1
+        const size_t ch = colsum_chunks(T);
+        float* p_b2 = ws_colsum[p];
+        float* p_ln2 = p_b2 + ch * H;
+        float* p_bo = p_ln2 + ch * 2 * H;
+        float* p_bqkv = p_bo + ch * H;
+        float* p_ln1 = p_bqkv + ch * 3 * H;
+        float* p_b1 = p_ln1 + ch * 2 * H;
+
+        // z = y + g W2 + b2
+        BP_HIP(hand_over(0));                                                                               // dz
+        if ((rc = gemm(sb + s_g, F, 1, dz, H, 0, G(BP_W2), H, F, H, T, nullptr, nullptr, 1, ss, true))) return rc;   // dW2
+        if ((rc = gemm(dz, H, 0, P(BP_W2), H, 1, big1, F, T, F, H, nullptr, nullptr, 0))) return rc;        // dg
+        {   // du = dg * gelu'(u + b1); db1 partials (folded with the other column sums below)
+            Scoped sc(this, BP_K_GELU_BWD, 0, 3.0 * T * F * esz);
+            BP_LAUNCH(launch_gelu_bwd(dtype, T, F, big1, sb + s_u, (const float*)P(BP_B1), big1, nullptr, p_b1,
+                                      stream));
+        }
+        BP_HIP(hand_over(1));                                                                               // du
+        if ((rc = gemm(sb + s_m, H, 1, big1, F, 0, G(BP_W1), F, H, F, T, nullptr, nullptr, 1, ss, true))) return rc;  // dW1
+        if ((rc = gemm(big1, F, 0, P(BP_W1), F, 1, h1, H, T, H, F, nullptr, nullptr, 0))) return rc;        // dm
         {   // dy = dz + LN2bwd(dm)
             Scoped sc(this, BP_K_LN_BWD, 0, 4 * unit);
-            BP_LAUNCH(launch_ln_bwd_rows(dtype, T, H, ws_h1, sb + s_y, (const float*)(sb + s_mean2),
-                                         (const float*)(sb + s_rstd2), (const float*)P(BP_LN2_G), dz,
-                                         ws_h2, stream));
-        }
-        {   // dgamma2, dbeta2, db2, dbo
-            Scoped sc(this, BP_K_COLSUM, 0, 0);
-            BP_LAUNCH(launch_colsum(dtype, T, H, ws_h1, sb + s_y, (const float*)(sb + s_mean2),
-                                    (const float*)(sb + s_rstd2), G(BP_LN2_B), G(BP_LN2_G), ws_colsum, stream));
-            BP_LAUNCH(launch_colsum(dtype, T, H, dz, nullptr, nullptr, nullptr, G(BP_B2), nullptr, ws_colsum, stream));
-            BP_LAUNCH(launch_colsum(dtype, T, H, ws_h2, nullptr, nullptr, nullptr, G(BP_BO), nullptr, ws_colsum, stream));
+            BP_LAUNCH(launch_ln_bwd_rows(dtype, T, H, h1, sb + s_y, (const float*)(sb + s_mean2),
+                                         (const float*)(sb + s_rstd2), (const float*)P(BP_LN2_G), dz, h2, stream));
         }
         // y = x + ctx Wo + bo
-        if ((rc = gemm(ws_h2, H, 0, P(BP_WO), H, 1, ws_h1, H, T, H, H, nullptr, nullptr, 0))) return rc;      // dctx
-        if ((rc = gemm(sb + s_ctx, H, 1, ws_h2, H, 0, G(BP_WO), H, H, H, T, nullptr, nullptr, 1))) return rc;  // dWo
+        BP_HIP(hand_over(2));                                                                               // dy
+        if ((rc = gemm(sb + s_ctx, H, 1, h2, H, 0, G(BP_WO), H, H, H, T, nullptr, nullptr, 1, ss, true))) return rc;  // dWo
+        if ((rc = gemm(h2, H, 0, P(BP_WO), H, 1, ws_h4, H, T, H, H, nullptr, nullptr, 0))) return rc;       // dctx
         {
             AttnArgs a{B, S, heads, d, causal ? 1 : 0, ln, sb + s_qkv, sb + s_ctx, (float*)(sb + s_lse),
-                       ws_h1, ws_big2, ws_delta};
+                       ws_h4, big2, ws_delta};
             Scoped sc(this, BP_K_ATTN_BWD, 8.0 * T * S * H * attn_c, 0);
             BP_LAUNCH(launch_attn_bwd(dtype, a, stream));
         }
         // qkv = a Wqkv + bqkv
-        if ((rc = gemm(ws_big2, 3 * H, 0, P(BP_WQKV), 3 * H, 1, ws_h1, H, T, H, 3 * H, nullptr, nullptr, 0))) return rc;  // da
-        if ((rc = gemm(sb + s_a, H, 1, ws_big2, 3 * H, 0, G(BP_WQKV), 3 * H, H, 3 * H, T, nullptr, nullptr, 1))) return rc;
-        {
+        BP_HIP(hand_over(3));                                                                               // dqkv
+        if ((rc = gemm(sb + s_a, H, 1, big2, 3 * H, 0, G(BP_WQKV), 3 * H, H, 3 * H, T, nullptr, nullptr, 1, ss, true)))
+            return rc;
+        if ((rc = gemm(big2, 3 * H, 0, P(BP_WQKV), 3 * H, 1, h5, H, T, H, 3 * H, nullptr, nullptr, 0))) return rc;  // da
+        BP_HIP(hand_over(4));                                                                               // da
+        {   // every bias and LayerNorm-parameter gradient of the layer in one batched reduction
+            ColsumBatch cb;
+            cb.n = 6;
+            cb.jobs[0] = ColsumJob{dz, nullptr, nullptr, nullptr, H, G(BP_B2), nullptr, p_b2};
+            cb.jobs[1] = ColsumJob{h1, sb + s_y, (const float*)(sb + s_mean2), (const float*)(sb + s_rstd2), H,
+                                   G(BP_LN2_B), G(BP_LN2_G), p_ln2};
+            cb.jobs[2] = ColsumJob{h2, nullptr, nullptr, nullptr, H, G(BP_BO), nullptr, p_bo};
+            cb.jobs[3] = ColsumJob{big2, nullptr, nullptr, nullptr, 3 * H, G(BP_BQKV), nullptr, p_bqkv};
+            cb.jobs[4] = ColsumJob{h5, sb + s_x, (const float*)(sb + s_mean1), (const float*)(sb + s_rstd1), H,
+                                   G(BP_LN1_B), G(BP_LN1_G), p_ln1};
+            cb.jobs[5] = ColsumJob{nullptr, nullptr, nullptr, nullptr, F, G(BP_B1), nullptr, p_b1};
             Scoped sc(this, BP_K_COLSUM, 0, 0);
-            BP_LAUNCH(launch_colsum(dtype, T, 3 * H, ws_big2, nullptr, nullptr, nullptr, G(BP_BQKV), nullptr,
-                                    ws_colsum, stream));
-            BP_LAUNCH(launch_colsum(dtype, T, H, ws_h1, sb + s_x, (const float*)(sb + s_mean1),
-                                    (const float*)(sb + s_rstd1), G(BP_LN1_B), G(BP_LN1_G), ws_colsum, stream));
+            BP_LAUNCH(launch_colsum_batch(dtype, T, cb, ss));
+        }
+        if (two) {
+            BP_HIP(hipEventRecord(ev_layer_done[p], ss));
+            layer_done_pending[p] = true;
+            if (l == 0 && L > 1) {
+                // grad_in may alias grad_out, which the side stream read for the top layer
+                const int tp = (L - 1) & 1;
+                if (tp != p && layer_done_pending[tp]) {
+                    BP_HIP(hipStreamWaitEvent(stream, ev_layer_done[tp], 0));
+                    layer_done_pending[tp] = false;
+                }
+            }
+            if (l == 0 && (L == 1 || ((L - 1) & 1) == p)) {
+                // same parity as the top layer (or a single layer): its record is the one just made
+                BP_HIP(hipStreamWaitEvent(stream, ev_layer_done[p], 0));
+                layer_done_pending[p] = false;
+            }
         }
         {   // dx = dy + LN1bwd(da)
             Scoped sc(this, BP_K_LN_BWD, 0, 4 * unit);
-            BP_LAUNCH(launch_ln_bwd_rows(dtype, T, H, ws_h1, sb + s_x, (const float*)(sb + s_mean1),
-                                         (const float*)(sb + s_rstd1), (const float*)P(BP_LN1_G), ws_h2,
-                                         dx, stream));
+            BP_LAUNCH(launch_ln_bwd_rows(dtype, T, H, h5, sb + s_x, (const float*)(sb + s_mean1),
+                                         (const float*)(sb + s_rstd1), (const float*)P(BP_LN1_G), h2, dx, stream));
         }
         dz = dx;
     }
+    if (two) {
+        // the stash may be handed to a new forward only after the side stream has read it
+        if (!slots[slot].side_done)
+            BP_HIP(hipEventCreateWithFlags(&slots[slot].side_done, hipEventDisableTiming));
+        BP_HIP(hipEventRecord(slots[slot].side_done, ss));
+        slots[slot].side_pending = true;
+        BP_HIP(hipEventRecord(ev_misc, ss));
+        call_done_pending = true;
+    }
+#undef BP_HIP
     slots[slot].live = false;
     return BP_OK;
 }
@@ -538,7 +649,8 @@ int bp_stage_backward_dir(bp_stage_t* st, int chunk, int mb, const void* grad_ou
 
 int bp_prof_enable(bp_stage_t* st, int on) {
     BP_ST(st);
-    hipStreamSynchronize(s_->stream);
+    int rc = s_->sync_all();
+    if (rc) return rc;
     s_->prof.reset();
     s_->prof.on = on != 0;
     return BP_OK;
@@ -547,7 +659,7 @@ int bp_prof_enable(bp_stage_t* st, int on) {
 int bp_prof_get(bp_stage_t* st, int kid, double* ms, long long* launches, double* flops, double* bytes) {
     BP_ST(st);
     if (kid < 0 || kid >= BP_N_KERNEL_IDS) return fail(BP_EINVAL, "kernel id %d out of range", kid);
-    hipStreamSynchronize(s_->stream);
+    if (s_->sync_all()) return BP_EHIP;
     s_->prof.collect();
     if (ms) *ms = s_->prof.ms_total[kid];
     if (launches) *launches = s_->prof.launches[kid];

@@ -114,24 +114,26 @@ __global__ __launch_bounds__(256) void ln_bwd_rows_kernel(const T* __restrict__ 
 }
 
 // ------------------------------------------------------------------ column reductions
-// Block = 4 waves covering 512 columns x kColsumRows rows; wave w takes rows w, w+4, ...
-// Partials are combined across the waves in LDS and written per row chunk; a second kernel
-// folds the chunks in a fixed order, so the result does not depend on scheduling.
-template <typename T, bool WITH_X>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ A,
-                                                             const T* __restrict__ X,
-                                                             const float* __restrict__ mean,
-                                                             const float* __restrict__ rstd,
-                                                             float* __restrict__ part, int rows,
-                                                             int N) {
+// Several reductions over [T, N_j] tensors run as one batch (blockIdx.z = job).  Block = 4 waves
+// covering 512 columns x kColsumRows rows; wave w takes rows w, w+4, ... and requests all of
+// them before consuming the first.  Partials are combined across the waves in LDS and written
+// per row chunk; a second kernel folds the chunks in a fixed order, so the result does not
+// depend on scheduling.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(ColsumBatch batch, int rows) {
     __shared__ float red[2][4][512];
+    const ColsumJob job = batch.jobs[blockIdx.z];
+    const int N = job.N;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int col = blockIdx.x * 512 + lane * 8;
+    if (blockIdx.x * 512 >= N || !job.A) return;        // uniform per block
+    const T* A = (const T*)job.A;
+    const T* X = (const T*)job.X;
+    const bool with_x = X != nullptr;
     const int r0 = blockIdx.y * kColsumRows;
     const int r1 = min(r0 + kColsumRows, rows);
     float sa[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (col < N) {
-        // all of this wave's rows are requested before the first one is consumed
         constexpr int RPW = kColsumRows / 4;
         float a[RPW][8], xv[RPW][8];
 #pragma unroll
@@ -139,15 +141,15 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
             const int r = r0 + w + 4 * j;
             if (r < r1) {
                 load8(A + (size_t)r * N + col, a[j]);
-                if (WITH_X) load8(X + (size_t)r * N + col, xv[j]);
+                if (with_x) load8(X + (size_t)r * N + col, xv[j]);
             }
         }
 #pragma unroll
         for (int j = 0; j < RPW; ++j) {
             const int r = r0 + w + 4 * j;
             if (r < r1) {
-                if (WITH_X) {
-                    const float mu = mean[r], rs = rstd[r];
+                if (with_x) {
+                    const float mu = job.mean[r], rs = job.rstd[r];
 #pragma unroll
                     for (int i = 0; i < 8; ++i) sx[i] += a[j][i] * (xv[j][i] - mu) * rs;
                 }
@@ -159,32 +161,43 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         red[0][w][lane * 8 + i] = sa[i];
-        if (WITH_X) red[1][w][lane * 8 + i] = sx[i];
+        red[1][w][lane * 8 + i] = sx[i];
     }
     __syncthreads();
-    const int nout = WITH_X ? 2 : 1;
+    const int nout = with_x ? 2 : 1;
     for (int e = threadIdx.x; e < 512 * nout; e += 256) {
         const int o = e / 512, c = e % 512;
         const int gc = blockIdx.x * 512 + c;
         if (gc < N) {
-            const float s = (red[o][0][c] + red[o][1][c]) + (red[o][2][c] + red[o][3][c]);
-            part[((size_t)blockIdx.y * nout + o) * N + gc] = s;
+            const float v = (red[o][0][c] + red[o][1][c]) + (red[o][2][c] + red[o][3][c]);
+            job.part[((size_t)blockIdx.y * nout + o) * N + gc] = v;
         }
     }
 }
 
-// out_k[c] += sum over chunks of part[chunk][k][c]
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part,
-                                                           int chunks, int nout, int N,
-                                                           float* __restrict__ out0,
-                                                           float* __restrict__ out1) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    const int o = blockIdx.y;
-    if (c >= N) return;
-    float s = 0.f;
-    for (int k = 0; k < chunks; ++k) s += part[((size_t)k * nout + o) * N + c];
-    float* out = o == 0 ? out0 : out1;
-    out[c] += s;
+// out_k[c] += sum over chunks of part[chunk][k][c].  Block = 64 columns x 4 chunk slices.
+__global__ __launch_bounds__(256) void colsum_final_kernel(ColsumBatch batch, int chunks) {
+    __shared__ float red[4][64];
+    const ColsumJob job = batch.jobs[blockIdx.y];
+    const int N = job.N;
+    if (blockIdx.x * 64 >= N || !job.part) return;
+    const int nout = job.out_ax ? 2 : 1;
+    const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + cl;
+    for (int o = 0; o < nout; ++o) {
+        float s = 0.f;
+        if (c < N) {
+#pragma unroll 4
+            for (int k = slice; k < chunks; k += 4) s += job.part[((size_t)k * nout + o) * N + c];
+        }
+        red[slice][cl] = s;
+        __syncthreads();
+        if (slice == 0 && c < N) {
+            float* out = o == 0 ? job.out_a : job.out_ax;
+            out[c] += (red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl]);
+        }
+        __syncthreads();
+    }
 }
 
 // ------------------------------------------------------------------ bias + GELU
@@ -386,35 +399,33 @@ hipError_t launch_ln_bwd_rows(int dtype, int T, int H, const void* dout, const v
                                   (const float*)res, (float*)dx, s);
 }
 
-template <typename T>
-static hipError_t colsum_dispatch(int T_, int N, const T* A, const T* X, const float* mean,
-                                  const float* rstd, float* out_a, float* out_ax, float* ws,
-                                  hipStream_t s) {
-    const int chunks = (int)colsum_chunks(T_);
-    dim3 grid((N + 511) / 512, chunks), block(256);
-    if (X)
-        hipLaunchKernelGGL((colsum_partial_kernel<T, true>), grid, block, 0, s, A, X, mean, rstd, ws,
-                           T_, N);
-    else
-        hipLaunchKernelGGL((colsum_partial_kernel<T, false>), grid, block, 0, s, A, X, mean, rstd,
-                           ws, T_, N);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const int nout = X ? 2 : 1;
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((N + 255) / 256, nout), block, 0, s, ws, chunks,
-                       nout, N, out_a, out_ax);
+hipError_t launch_colsum_batch(int dtype, int T, const ColsumBatch& batch, hipStream_t s) {
+    if (T <= 0 || batch.n <= 0 || batch.n > kMaxColsumJobs) return hipErrorInvalidValue;
+    const int chunks = (int)colsum_chunks(T);
+    int max_n = 0;
+    bool any_partial = false;
+    for (int j = 0; j < batch.n; ++j) {
+        if (batch.jobs[j].N % 8) return hipErrorInvalidValue;
+        max_n = max_n > batch.jobs[j].N ? max_n : batch.jobs[j].N;
+        any_partial |= batch.jobs[j].A != nullptr;
+    }
+    if (any_partial) {
+        dim3 grid((max_n + 511) / 512, chunks, batch.n), block(256);
+        if (dtype == BF16) hipLaunchKernelGGL((colsum_partial_kernel<bf16_t>), grid, block, 0, s, batch, T);
+        else hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, block, 0, s, batch, T);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((max_n + 63) / 64, batch.n), dim3(256), 0, s, batch, chunks);
     return hipGetLastError();
 }
 
 hipError_t launch_colsum(int dtype, int T, int N, const void* A, const void* X, const float* mean,
-                         const float* rstd, float* out_a, float* out_ax, float* ws,
-                         hipStream_t s) {
-    if (N % 8 || T <= 0) return hipErrorInvalidValue;
-    if (dtype == BF16)
-        return colsum_dispatch<bf16_t>(T, N, (const bf16_t*)A, (const bf16_t*)X, mean, rstd, out_a,
-                                       out_ax, ws, s);
-    return colsum_dispatch<float>(T, N, (const float*)A, (const float*)X, mean, rstd, out_a, out_ax,
-                                  ws, s);
+                         const float* rstd, float* out_a, float* out_ax, float* ws, hipStream_t s) {
+    ColsumBatch b;
+    b.n = 1;
+    b.jobs[0] = ColsumJob{A, X, mean, rstd, N, out_a, X ? out_ax : nullptr, ws};
+    return launch_colsum_batch(dtype, T, b, s);
 }
 
 hipError_t launch_gelu_fwd(int dtype, int T, int F, const void* u, const float* bias, void* g,
@@ -432,6 +443,7 @@ hipError_t launch_gelu_fwd(int dtype, int T, int F, const void* u, const float* 
 
 hipError_t launch_gelu_bwd(int dtype, int T, int F, const void* dg, const void* u,
                            const float* bias, void* du, float* dbias, float* ws, hipStream_t s) {
+    // dbias == nullptr: leave the per-chunk partials in ws for a later batched final reduction
     if (F % 8 || T <= 0) return hipErrorInvalidValue;
     const int chunks = (int)colsum_chunks(T);
     dim3 grid((F + 511) / 512, chunks), block(256);
@@ -442,9 +454,11 @@ hipError_t launch_gelu_bwd(int dtype, int T, int F, const void* dg, const void* 
         hipLaunchKernelGGL((gelu_bwd_kernel<float>), grid, block, 0, s, (const float*)dg,
                            (const float*)u, bias, (float*)du, ws, T, F);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((F + 255) / 256, 1), block, 0, s, ws, chunks, 1, F,
-                       dbias, (float*)nullptr);
+    if (e != hipSuccess || !dbias) return e;
+    ColsumBatch b;
+    b.n = 1;
+    b.jobs[0] = ColsumJob{nullptr, nullptr, nullptr, nullptr, F, dbias, nullptr, ws};
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((F + 63) / 64, 1), block, 0, s, b, chunks);
     return hipGetLastError();
 }
 
