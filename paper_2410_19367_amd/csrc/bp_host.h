@@ -63,7 +63,9 @@ struct Stage {
     // parameters (matrices in the storage dtype, vectors fp32) and fp32 gradients per direction
     void* params = nullptr;
     float* grads[2] = {nullptr, nullptr};
-    size_t p_off[BP_N_TENSORS], g_off[BP_N_TENSORS], p_layer_bytes = 0, g_layer_bytes = 0;
+    // Each weight matrix is also kept transposed ([out,in]) so that the forward GEMMs read both
+    // operands contraction-major like the data-gradient GEMMs do; slots BP_N_TENSORS.. hold them.
+    size_t p_off[BP_N_TENSORS + 4], g_off[BP_N_TENSORS], p_layer_bytes = 0, g_layer_bytes = 0;
 
     // stash of one layer: byte offsets inside a slot
     size_t s_x, s_a, s_qkv, s_ctx, s_y, s_m, s_u, s_g, s_mean1, s_rstd1, s_mean2, s_rstd2, s_lse;
@@ -95,6 +97,8 @@ struct Stage {
     size_t tensor_elems(int id) const;
     static bool tensor_is_matrix(int id);
     void* param(int chunk, int layer, int id) const;
+    void* param_t(int chunk, int layer, int id) const;   // transposed copy of a weight matrix
+    static int transposed_slot(int id);
     float* grad(int dir, int chunk, int layer, int id) const;
     int check_tensor(int chunk, int layer, int id, size_t n) const;
 

@@ -104,6 +104,8 @@ hipError_t launch_loss(int dtype, size_t n, const void* z, const void* target, f
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t stream);
 hipError_t launch_add_f32(float* dst, const float* src, size_t n, hipStream_t stream);   // dst += src
 // host fp32 staging (already on device as fp32) -> storage dtype
+// dst[cols][rows] = src[rows][cols]^T, storage dtype
+hipError_t launch_transpose(int dtype, int rows, int cols, const void* src, void* dst, hipStream_t stream);
 hipError_t launch_cast_from_f32(int dtype, const float* src, void* dst, size_t n, hipStream_t stream);
 
 }  // namespace bp

@@ -151,6 +151,11 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
         poff += align_up(n * (tensor_is_matrix(t) ? st->esz : sizeof(float)), 256);
         goff += align_up(n * sizeof(float), 256);
     }
+    for (int t = 0; t < BP_N_TENSORS; ++t) {
+        if (!tensor_is_matrix(t)) continue;
+        st->p_off[transposed_slot(t)] = poff;
+        poff += align_up(st->tensor_elems(t) * st->esz, 256);
+    }
     st->p_layer_bytes = poff;
     st->g_layer_bytes = goff;
     const size_t n_layers = (size_t)st->n_chunks * st->L;
@@ -246,6 +251,12 @@ Stage::~Stage() {
     hipFree(sched_act); hipFree(sched_grad); hipFree(sched_loss);
 }
 
+int Stage::transposed_slot(int id) {
+    return BP_N_TENSORS + (id == BP_WQKV ? 0 : id == BP_WO ? 1 : id == BP_W1 ? 2 : 3);
+}
+void* Stage::param_t(int chunk, int layer, int id) const {
+    return (char*)params + ((size_t)chunk * L + layer) * p_layer_bytes + p_off[transposed_slot(id)];
+}
 void* Stage::param(int chunk, int layer, int id) const {
     return (char*)params + ((size_t)chunk * L + layer) * p_layer_bytes + p_off[id];
 }
@@ -270,14 +281,20 @@ int Stage::set_param(int chunk, int layer, int id, const float* host, size_t n) 
     if (!host) return fail(BP_EINVAL, "host pointer is null");
     void* dst = param(chunk, layer, id);
     hipError_t e;
+    // rows x cols of the [in, out] matrix
+    const int rows = id == BP_W2 ? F : H;
+    const int cols = id == BP_WQKV ? 3 * H : id == BP_W1 ? F : H;
     if (!tensor_is_matrix(id) || dtype == BP_F32) {
         e = hipMemcpyAsync(dst, host, n * sizeof(float), hipMemcpyHostToDevice, stream);
+        if (e == hipSuccess && tensor_is_matrix(id))
+            e = launch_transpose(dtype, rows, cols, dst, param_t(chunk, layer, id), stream);
         if (e == hipSuccess) e = hipStreamSynchronize(stream);
     } else {
         float* tmp = nullptr;
         if ((rc = dev_alloc((void**)&tmp, n * sizeof(float)))) return rc;
         e = hipMemcpyAsync(tmp, host, n * sizeof(float), hipMemcpyHostToDevice, stream);
         if (e == hipSuccess) e = launch_cast_from_f32(dtype, tmp, dst, n, stream);
+        if (e == hipSuccess) e = launch_transpose(dtype, rows, cols, dst, param_t(chunk, layer, id), stream);
         if (e == hipSuccess) e = hipStreamSynchronize(stream);
         hipFree(tmp);
     }
@@ -420,7 +437,7 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
                                     (float*)(sb + s_mean1), (float*)(sb + s_rstd1),
                                     l == 0 ? sb + s_x : nullptr, stream));
         }
-        if ((rc = gemm(sb + s_a, H, 0, param(chunk, l, BP_WQKV), 3 * H, 0, sb + s_qkv, 3 * H, T, 3 * H, H,
+        if ((rc = gemm(sb + s_a, H, 0, param_t(chunk, l, BP_WQKV), H, 1, sb + s_qkv, 3 * H, T, 3 * H, H,
                        (const float*)param(chunk, l, BP_BQKV), nullptr, 0))) return rc;
         {
             AttnArgs a{B, S, heads, d, causal ? 1 : 0, ln, sb + s_qkv, sb + s_ctx, (float*)(sb + s_lse),
@@ -428,7 +445,7 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
             Scoped sc(this, BP_K_ATTN_FWD, 4.0 * T * S * H * attn_c, 0);
             BP_LAUNCH(launch_attn_fwd(dtype, a, stream));
         }
-        if ((rc = gemm(sb + s_ctx, H, 0, param(chunk, l, BP_WO), H, 0, sb + s_y, H, T, H, H,
+        if ((rc = gemm(sb + s_ctx, H, 0, param_t(chunk, l, BP_WO), H, 1, sb + s_y, H, T, H, H,
                        (const float*)param(chunk, l, BP_BO), x, 0))) return rc;
         {
             Scoped sc(this, BP_K_LN_FWD, 0, 2 * unit);
@@ -436,14 +453,14 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
                                     (const float*)param(chunk, l, BP_LN2_B), eps, sb + s_m,
                                     (float*)(sb + s_mean2), (float*)(sb + s_rstd2), nullptr, stream));
         }
-        if ((rc = gemm(sb + s_m, H, 0, param(chunk, l, BP_W1), F, 0, sb + s_u, F, T, F, H, nullptr, nullptr, 0)))
+        if ((rc = gemm(sb + s_m, H, 0, param_t(chunk, l, BP_W1), H, 1, sb + s_u, F, T, F, H, nullptr, nullptr, 0)))
             return rc;
         {
             Scoped sc(this, BP_K_GELU_FWD, 0, 2.0 * T * F * esz);
             BP_LAUNCH(launch_gelu_fwd(dtype, T, F, sb + s_u, (const float*)param(chunk, l, BP_B1),
                                       sb + s_g, stream));
         }
-        if ((rc = gemm(sb + s_g, F, 0, param(chunk, l, BP_W2), H, 0, z, H, T, H, F,
+        if ((rc = gemm(sb + s_g, F, 0, param_t(chunk, l, BP_W2), F, 1, z, H, T, H, F,
                        (const float*)param(chunk, l, BP_B2), sb + s_y, 0))) return rc;
     }
     return BP_OK;

@@ -334,6 +334,20 @@ __global__ __launch_bounds__(256) void cast_from_f32_kernel(const float* src, T*
         dst[i] = from_float<T>(src[i]);
 }
 
+// dst[c][r] = src[r][c] through a padded 32x32 LDS tile
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ src, T* __restrict__ dst,
+                                                        int rows, int cols) {
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = src[(size_t)(r0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && r0 + tx < rows) dst[(size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+
 // ------------------------------------------------------------------ launchers
 static inline int grid_for(size_t work_items, int per_block, int cap = 256 * 16) {
     size_t b = (work_items + per_block - 1) / per_block;
@@ -488,6 +502,16 @@ hipError_t launch_add_f32(float* dst, const float* src, size_t n, hipStream_t s)
     hipLaunchKernelGGL(add_f32_kernel, dim3(grid_for(n, 256 * 4)), dim3(256), 0, s, dst, src, n);
     return hipGetLastError();
 }
+hipError_t launch_transpose(int dtype, int rows, int cols, const void* src, void* dst, hipStream_t s) {
+    if (rows <= 0 || cols <= 0) return hipErrorInvalidValue;
+    dim3 grid((cols + 31) / 32, (rows + 31) / 32), block(256);
+    if (dtype == BF16)
+        hipLaunchKernelGGL((transpose_kernel<bf16_t>), grid, block, 0, s, (const bf16_t*)src, (bf16_t*)dst, rows, cols);
+    else
+        hipLaunchKernelGGL((transpose_kernel<float>), grid, block, 0, s, (const float*)src, (float*)dst, rows, cols);
+    return hipGetLastError();
+}
+
 hipError_t launch_cast_from_f32(int dtype, const float* src, void* dst, size_t n, hipStream_t s) {
     if (n == 0) return hipSuccess;
     const int grid = grid_for(n, 256 * 4);
