@@ -90,7 +90,7 @@ struct AttnArgs {
 };
 hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attn_bwd(int dtype, const AttnArgs& a, hipStream_t stream);
-bool attn_mfma_supported(const AttnArgs& a);                       // bf16, head dim 64/128, S % 128 == 0
+bool attn_mfma_supported(const AttnArgs& a);                       // bf16, head dim 64/128, S % 64 == 0
 hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t stream);
 hipError_t launch_attn_fwd_generic(int dtype, const AttnArgs& a, hipStream_t stream);

@@ -93,33 +93,54 @@ __device__ __forceinline__ bf16x8 acc_to_b(const f32x16& a, int half) {
 // row index inside a 32-row accumulator tile held in register v by a lane of half h
 __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
+// Heavy-first, then light-last block order for causal masks: the first half of the grid walks the
+// query (or key) blocks from the most expensive down, the second half from the cheapest up, so the
+// two blocks that share a CU's two slots add up to roughly the same work everywhere.
+__device__ __forceinline__ void block_coords(int nblk, int heads, bool causal, bool heavy_is_last_index,
+                                            int& blk, int& head, int& b) {
+    const int per = nblk * heads;             // blocks per batch entry
+    const int lin = blockIdx.x % per;
+    b = blockIdx.x / per;
+    int i = lin / heads;                      // position in the work-sorted order
+    head = lin % heads;
+    if (causal) {
+        // positions 0, 1, 2, ... -> heaviest, lightest, 2nd heaviest, 2nd lightest, ... folded so that
+        // the first half of the launch is the heavy half
+        const int half = (nblk + 1) / 2;
+        const int rank = i < half ? i : nblk - 1 - (i - half);      // 0 = heaviest
+        blk = heavy_is_last_index ? nblk - 1 - rank : rank;
+    } else {
+        blk = i;
+    }
+}
+
 // =====================================================================================
-// Forward.  Block = 4 waves x 32 queries; K/V tiles of 64 keys, two LDS stages.
+// Forward.  Block = 4 waves = 2 groups of 32 queries x 2 halves of every 64-key tile; each wave
+// keeps its own online-softmax state and the two halves are merged through LDS at the end.
 // =====================================================================================
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float scale) {
     constexpr int NW = 4, KS = D / 16, DT = D / 32;
     constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE;   // K then V
-    constexpr int LPT = 2 * dma_per_wave<D, NW>();
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int qg = wave >> 1, kh = wave & 1;
     const int h = lane >> 5;
-    const int qblk = a.causal ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;   // heavy blocks first
-    const int head = blockIdx.y, b = blockIdx.z;
+    int qblk, head, b;
+    block_coords(a.S / 64, a.heads, a.causal != 0, true, qblk, head, b);
     const int H = a.heads * D, ld = 3 * H;
     const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * D;
     const bf16_t* kbase = qkv + H;
     const bf16_t* vbase = qkv + 2 * H;
-    const int q_wave = qblk * 128 + wave * 32;
+    const int q_wave = qblk * 64 + qg * 32;
     const int q_lane = q_wave + (lane & 31);
     const int klen = a.causal ? a.S : (a.lens ? a.lens[b] : a.S);
-    const int kend = a.causal ? min(qblk * 128 + 128, a.S) : klen;     // keys [0, kend) matter
+    const int kend = a.causal ? qblk * 64 + 64 : klen;     // keys [0, kend) matter to this block
     const int nt = (kend + 63) / 64;
     const float c = scale * kLog2e;
 
-    // Q as the B operand of S^T = K Q^T: lane = query, 8 consecutive d per k16 step
     bf16x8 qf[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s)
@@ -145,79 +166,93 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
             dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows);
             dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows);
         }
-        if (a.causal && k0 > q_wave + 31) continue;     // every key of this tile is masked for this wave
+        const int kw = k0 + 32 * kh;                    // first key of this wave's half
+        if ((a.causal && kw > q_wave + 31) || kw >= klen) continue;     // nothing unmasked for this wave
         const char* sk = smem + (t & 1) * STAGE;
         const char* sv = sk + TILE;
 
-        // S^T (64 keys x 32 queries)
-        f32x16 st2[2];
+        // S^T (32 keys x 32 queries)
+        f32x16 st2;
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+        for (int v = 0; v < 16; ++v) st2[v] = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) st2[kt][v] = 0.f;
-#pragma unroll
-            for (int s = 0; s < KS; ++s)
-                st2[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, kt * 32, s, lane), qf[s],
-                                                                  st2[kt], 0, 0, 0);
-        }
-        // scale to the log2 domain, mask, running max
-        const bool need_mask = (a.causal && k0 + 63 > q_wave) || (k0 + 64 > klen);
+        for (int s = 0; s < KS; ++s)
+            st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, 32 * kh, s, lane), qf[s], st2, 0, 0, 0);
+        const bool need_mask = (a.causal && kw + 31 > q_wave) || (kw + 32 > klen);
         float mx = -INFINITY;
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float sv_ = st2[kt][v] * c;
-                if (need_mask) {
-                    const int key = k0 + kt * 32 + acc_row(v, h);
-                    if ((a.causal && key > q_lane) || key >= klen) sv_ = -INFINITY;
-                }
-                st2[kt][v] = sv_;
-                mx = fmaxf(mx, sv_);
+        for (int v = 0; v < 16; ++v) {
+            float sv_ = st2[v] * c;
+            if (need_mask) {
+                const int key = kw + acc_row(v, h);
+                if ((a.causal && key > q_lane) || key >= klen) sv_ = -INFINITY;
             }
+            st2[v] = sv_;
+            mx = fmaxf(mx, sv_);
+        }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m, mx);
-        const float alpha = exp2f(m - m_new);
+        // a row whose keys are all masked so far keeps m = -inf; avoid inf - inf
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = exp2f(m - m_use);
         m = m_new;
         float ps = 0.f;
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = exp2f(st2[kt][v] - m_new);
-                st2[kt][v] = p;
-                ps += p;
-            }
+        for (int v = 0; v < 16; ++v) {
+            const float p = exp2f(st2[v] - m_use);
+            st2[v] = p;
+            ps += p;
+        }
         lsum = lsum * alpha + ps;
 #pragma unroll
         for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
             for (int v = 0; v < 16; ++v) ot[t2][v] *= alpha;
-        // O^T (D x 32 queries) += V^T P^T
+        // O^T (D x 32 queries) += V^T P^T over this wave's 32 keys
 #pragma unroll
-        for (int s2 = 0; s2 < 4; ++s2) {
-            const bf16x8 pb = acc_to_b(st2[s2 >> 1], s2 & 1);
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const bf16x8 pb = acc_to_b(st2, s2);
 #pragma unroll
             for (int t2 = 0; t2 < DT; ++t2)
-                ot[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<D>(sv, 16 * s2, t2 * 32, lane), pb,
-                                                                 ot[t2], 0, 0, 0);
+                ot[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    frag_cols<D>(sv, 32 * kh + 16 * s2, t2 * 32, lane), pb, ot[t2], 0, 0, 0);
         }
     }
 
-    const float l = lsum + __shfl_xor(lsum, 32, 64);
+    // merge the two key halves: the odd wave of each pair hands (m, l, O^T) over through LDS
+    float l = lsum + __shfl_xor(lsum, 32, 64);
+    __syncthreads();                                    // all tile reads are over; LDS is free
+    float* xo = (float*)smem + qg * (DT * 16 * 64 + 128);   // [DT*16][64 lanes] + m[64] + l[64]
+    if (kh == 1) {
+#pragma unroll
+        for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) xo[(t2 * 16 + v) * 64 + lane] = ot[t2][v];
+        xo[DT * 16 * 64 + lane] = m;
+        xo[DT * 16 * 64 + 64 + lane] = l;
+    }
+    __syncthreads();
+    if (kh == 1) return;
+    const float m1 = xo[DT * 16 * 64 + lane], l1 = xo[DT * 16 * 64 + 64 + lane];
+    const float mm = fmaxf(m, m1);                      // finite: key 0 (or any valid key) is in half 0 or 1
+    const float a0 = exp2f(m - mm), a1 = exp2f(m1 - mm);
+    l = l * a0 + l1 * a1;
     const float inv = 1.f / l;
     bf16_t* out = (bf16_t*)a.ctx + ((size_t)b * a.S + q_lane) * H + head * D;
 #pragma unroll
     for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            // registers 4g..4g+3 are four consecutive d
+            float o4[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                o4[e] = (ot[t2][4 * g + e] * a0 + xo[(t2 * 16 + 4 * g + e) * 64 + lane] * a1) * inv;
             uint2 pk;
-            pk.x = pack_bf16x2(ot[t2][4 * g] * inv, ot[t2][4 * g + 1] * inv);
-            pk.y = pack_bf16x2(ot[t2][4 * g + 2] * inv, ot[t2][4 * g + 3] * inv);
+            pk.x = pack_bf16x2(o4[0], o4[1]);
+            pk.y = pack_bf16x2(o4[2], o4[3]);
             *reinterpret_cast<uint2*>(out + t2 * 32 + 8 * g + 4 * h) = pk;
         }
-    if (h == 0) a.lse[((size_t)b * a.heads + head) * a.S + q_lane] = (m + log2f(l)) * kLn2;
+    if (h == 0) a.lse[((size_t)b * a.heads + head) * a.S + q_lane] = (mm + log2f(l)) * kLn2;
 }
 
 // =====================================================================================
@@ -244,9 +279,10 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(AttnArgs a, int D) {
 }
 
 // =====================================================================================
-// Backward, part 2: dQ.  Same structure as the forward: lane <-> query.
+// Backward, part 2: dQ.  Same decomposition as the forward (lane <-> query, two key halves):
 //   S^T = K Q^T, P^T = exp(S^T - lse), dP^T = V dO^T, dS^T = P^T (dP^T - delta),
 //   dQ^T (D x 32) += K^T dS^T         (K tile read plainly for S^T and transposed for dQ^T)
+// The two halves' partial dQ^T are added through LDS at the end.
 // =====================================================================================
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, float scale) {
@@ -256,17 +292,18 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int qg = wave >> 1, kh = wave & 1;
     const int h = lane >> 5;
-    const int qblk = a.causal ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
-    const int head = blockIdx.y, b = blockIdx.z;
+    int qblk, head, b;
+    block_coords(a.S / 64, a.heads, a.causal != 0, true, qblk, head, b);
     const int H = a.heads * D, ld = 3 * H;
     const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * D;
     const bf16_t* kbase = qkv + H;
     const bf16_t* vbase = qkv + 2 * H;
-    const int q_wave = qblk * 128 + wave * 32;
+    const int q_wave = qblk * 64 + qg * 32;
     const int q_lane = q_wave + (lane & 31);
     const int klen = a.causal ? a.S : (a.lens ? a.lens[b] : a.S);
-    const int kend = a.causal ? min(qblk * 128 + 128, a.S) : klen;
+    const int kend = a.causal ? qblk * 64 + 64 : klen;
     const int nt = (kend + 63) / 64;
     const float c = scale * kLog2e;
 
@@ -300,92 +337,107 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
             dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows);
             dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows);
         }
-        if (a.causal && k0 > q_wave + 31) continue;
+        const int kw = k0 + 32 * kh;
+        if ((a.causal && kw > q_wave + 31) || kw >= klen) continue;
         const char* sk = smem + (t & 1) * STAGE;
         const char* sv = sk + TILE;
-        const bool need_mask = (a.causal && k0 + 63 > q_wave) || (k0 + 64 > klen);
-        f32x16 ds[2];
+        const bool need_mask = (a.causal && kw + 31 > q_wave) || (kw + 32 > klen);
+        f32x16 sacc, dp;
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            f32x16 sacc, dp;
+        for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dp[v] = 0.f; }
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, kt * 32, s, lane), qf[s], sacc, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sv, kt * 32, s, lane), dof[s], dp, 0, 0, 0);
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float p = exp2f(sacc[v] * c - lse2);
-                if (need_mask) {
-                    const int key = k0 + kt * 32 + acc_row(v, h);
-                    if ((a.causal && key > q_lane) || key >= klen) p = 0.f;
-                }
-                ds[kt][v] = p * (dp[v] - delta);
-            }
+        for (int s = 0; s < KS; ++s) {
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, 32 * kh, s, lane), qf[s], sacc, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sv, 32 * kh, s, lane), dof[s], dp, 0, 0, 0);
         }
 #pragma unroll
-        for (int s2 = 0; s2 < 4; ++s2) {
-            const bf16x8 db = acc_to_b(ds[s2 >> 1], s2 & 1);
+        for (int v = 0; v < 16; ++v) {
+            float p = exp2f(sacc[v] * c - lse2);
+            if (need_mask) {
+                const int key = kw + acc_row(v, h);
+                if ((a.causal && key > q_lane) || key >= klen) p = 0.f;
+            }
+            dp[v] = p * (dp[v] - delta);            // dS^T
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const bf16x8 db = acc_to_b(dp, s2);
 #pragma unroll
             for (int t2 = 0; t2 < DT; ++t2)
-                dq[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<D>(sk, 16 * s2, t2 * 32, lane), db,
-                                                                 dq[t2], 0, 0, 0);
+                dq[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    frag_cols<D>(sk, 32 * kh + 16 * s2, t2 * 32, lane), db, dq[t2], 0, 0, 0);
         }
     }
+    __syncthreads();
+    float* xo = (float*)smem + qg * (DT * 16 * 64);
+    if (kh == 1) {
+#pragma unroll
+        for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) xo[(t2 * 16 + v) * 64 + lane] = dq[t2][v];
+    }
+    __syncthreads();
+    if (kh == 1) return;
     bf16_t* out = (bf16_t*)a.dqkv + ((size_t)b * a.S + q_lane) * ld + head * D;
 #pragma unroll
     for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
+            float o4[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                o4[e] = (dq[t2][4 * g + e] + xo[(t2 * 16 + 4 * g + e) * 64 + lane]) * scale;
             uint2 pk;
-            pk.x = pack_bf16x2(dq[t2][4 * g] * scale, dq[t2][4 * g + 1] * scale);
-            pk.y = pack_bf16x2(dq[t2][4 * g + 2] * scale, dq[t2][4 * g + 3] * scale);
+            pk.x = pack_bf16x2(o4[0], o4[1]);
+            pk.y = pack_bf16x2(o4[2], o4[3]);
             *reinterpret_cast<uint2*>(out + t2 * 32 + 8 * g + 4 * h) = pk;
         }
 }
 
 // =====================================================================================
-// Backward, part 3: dK and dV.  Block = 4 waves x 32 keys; Q/dO tiles of 64 queries stream by.
+// Backward, part 3: dK and dV.  Block = 4 waves = 2 groups of 32 keys x 2 halves of every
+// 64-query tile of Q / dO that streams by.
 //   S = Q K^T (lane <-> key), P = exp(S - lse[q]), dP = dO V^T, dS = P (dP - delta[q]),
 //   dV^T (D x 32 keys) += dO^T P,   dK^T (D x 32 keys) += Q^T dS
+// The two query halves' partial sums are added through LDS at the end.
 // =====================================================================================
 template <int D>
-__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, float scale) {
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, float scale) {
     constexpr int NW = 4, KS = D / 16, DT = D / 32;
     constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE + 512;   // Q, dO, then lse[64], delta[64]
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kg = wave >> 1, qh = wave & 1;
     const int h = lane >> 5;
-    const int kblk = blockIdx.x;
-    const int head = blockIdx.y, b = blockIdx.z;
+    int kblk, head, b;
+    block_coords(a.S / 64, a.heads, a.causal != 0, false, kblk, head, b);   // key block 0 is the heaviest
     const int H = a.heads * D, ld = 3 * H;
     const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * D;
     const bf16_t* dobase = (const bf16_t*)a.dctx + (size_t)b * a.S * H + head * D;
-    const int k_wave = kblk * 128 + wave * 32;
+    const int k_wave = kblk * 64 + kg * 32;
     const int k_lane = k_wave + (lane & 31);
     const int klen = a.causal ? a.S : (a.lens ? a.lens[b] : a.S);
     bf16_t* dk_out = (bf16_t*)a.dqkv + ((size_t)b * a.S + k_lane) * ld + H + head * D;
     bf16_t* dv_out = dk_out + H;
-    if (kblk * 128 >= klen) {      // the whole block of keys is padding: no query attends it
-        const uint2 z = make_uint2(0u, 0u);
+    if (kblk * 64 >= klen) {      // the whole block of keys is padding: no query attends it
+        if (qh == 0) {
+            const uint2 z = make_uint2(0u, 0u);
 #pragma unroll
-        for (int t2 = 0; t2 < DT; ++t2)
+            for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                *reinterpret_cast<uint2*>(dk_out + t2 * 32 + 8 * g + 4 * h) = z;
-                *reinterpret_cast<uint2*>(dv_out + t2 * 32 + 8 * g + 4 * h) = z;
-            }
+                for (int g = 0; g < 4; ++g) {
+                    *reinterpret_cast<uint2*>(dk_out + t2 * 32 + 8 * g + 4 * h) = z;
+                    *reinterpret_cast<uint2*>(dv_out + t2 * 32 + 8 * g + 4 * h) = z;
+                }
+        }
         return;
     }
     const float c = scale * kLog2e;
     const float* lse = a.lse + ((size_t)b * a.heads + head) * a.S;
     const float* dlt = a.delta + ((size_t)b * a.heads + head) * a.S;
 
-    // K and V of this lane's key as B operands (lane = key column, 8 consecutive d per step)
     bf16x8 kf[KS], vf[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -398,8 +450,7 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dkv_mfma_kerne
 #pragma unroll
         for (int v = 0; v < 16; ++v) { dk[t][v] = 0.f; dv[t][v] = 0.f; }
 
-    // queries that can attend this block's keys: causal -> q >= first key of the block
-    const int t0 = a.causal ? (kblk * 128) / 64 : 0;
+    const int t0 = a.causal ? kblk : 0;        // first 64-query tile that can see this block's keys
     const int nt = a.S / 64;
 
     auto load_stage = [&](int t, char* st) {
@@ -416,54 +467,72 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dkv_mfma_kerne
         BP_WAIT_VMCNT(0);
         __syncthreads();
         if (t + 1 < nt) load_stage(t + 1, smem + ((t + 1) & 1) * STAGE);
-        if (a.causal && q0 + 63 < k_wave) continue;      // no query of this tile reaches this wave's keys
+        const int qw = q0 + 32 * qh;                     // first query of this wave's half
+        if (a.causal && qw + 31 < k_wave) continue;      // no query of this half reaches this wave's keys
         const char* sq = smem + (t & 1) * STAGE;
         const char* sdo = sq + TILE;
-        const float* s_lse = (const float*)(sq + 2 * TILE);
-        const float* s_dlt = s_lse + 64;
-        const bool need_mask = a.causal && q0 < k_wave + 31;
-        f32x16 pacc[2], ds[2];
+        const float* s_lse = (const float*)(sq + 2 * TILE) + 32 * qh;
+        const float* s_dlt = (const float*)(sq + 2 * TILE) + 64 + 32 * qh;
+        const bool need_mask = a.causal && qw < k_wave + 31;
+        f32x16 sacc, dp;
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            f32x16 sacc, dp;
+        for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dp[v] = 0.f; }
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sq, qt * 32, s, lane), kf[s], sacc, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sdo, qt * 32, s, lane), vf[s], dp, 0, 0, 0);
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int qi = qt * 32 + acc_row(v, h);
-                float p = exp2f(sacc[v] * c - s_lse[qi]);
-                if (need_mask && k_lane > q0 + qi) p = 0.f;
-                if (k_lane >= klen) p = 0.f;
-                pacc[qt][v] = p;
-                ds[qt][v] = p * (dp[v] - s_dlt[qi]);
-            }
+        for (int s = 0; s < KS; ++s) {
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sq, 32 * qh, s, lane), kf[s], sacc, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sdo, 32 * qh, s, lane), vf[s], dp, 0, 0, 0);
         }
 #pragma unroll
-        for (int s2 = 0; s2 < 4; ++s2) {
-            const bf16x8 pb = acc_to_b(pacc[s2 >> 1], s2 & 1);
-            const bf16x8 db = acc_to_b(ds[s2 >> 1], s2 & 1);
+        for (int v = 0; v < 16; ++v) {
+            const int qi = acc_row(v, h);
+            float p = exp2f(sacc[v] * c - s_lse[qi]);
+            if (need_mask && k_lane > qw + qi) p = 0.f;
+            if (k_lane >= klen) p = 0.f;
+            sacc[v] = p;                                 // P
+            dp[v] = p * (dp[v] - s_dlt[qi]);             // dS
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const bf16x8 pb = acc_to_b(sacc, s2);
+            const bf16x8 db = acc_to_b(dp, s2);
 #pragma unroll
             for (int t2 = 0; t2 < DT; ++t2) {
-                dv[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<D>(sdo, 16 * s2, t2 * 32, lane), pb, dv[t2], 0, 0, 0);
-                dk[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<D>(sq, 16 * s2, t2 * 32, lane), db, dk[t2], 0, 0, 0);
+                dv[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    frag_cols<D>(sdo, 32 * qh + 16 * s2, t2 * 32, lane), pb, dv[t2], 0, 0, 0);
+                dk[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    frag_cols<D>(sq, 32 * qh + 16 * s2, t2 * 32, lane), db, dk[t2], 0, 0, 0);
             }
         }
     }
+    __syncthreads();
+    float* xo = (float*)smem + kg * (2 * DT * 16 * 64);
+    if (qh == 1) {
+#pragma unroll
+        for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                xo[(t2 * 16 + v) * 64 + lane] = dk[t2][v];
+                xo[((DT + t2) * 16 + v) * 64 + lane] = dv[t2][v];
+            }
+    }
+    __syncthreads();
+    if (qh == 1) return;
 #pragma unroll
     for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
+            float k4[4], v4[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                k4[e] = (dk[t2][4 * g + e] + xo[(t2 * 16 + 4 * g + e) * 64 + lane]) * scale;
+                v4[e] = dv[t2][4 * g + e] + xo[((DT + t2) * 16 + 4 * g + e) * 64 + lane];
+            }
             uint2 pk;
-            pk.x = pack_bf16x2(dk[t2][4 * g] * scale, dk[t2][4 * g + 1] * scale);
-            pk.y = pack_bf16x2(dk[t2][4 * g + 2] * scale, dk[t2][4 * g + 3] * scale);
+            pk.x = pack_bf16x2(k4[0], k4[1]);
+            pk.y = pack_bf16x2(k4[2], k4[3]);
             *reinterpret_cast<uint2*>(dk_out + t2 * 32 + 8 * g + 4 * h) = pk;
-            pk.x = pack_bf16x2(dv[t2][4 * g], dv[t2][4 * g + 1]);
-            pk.y = pack_bf16x2(dv[t2][4 * g + 2], dv[t2][4 * g + 3]);
+            pk.x = pack_bf16x2(v4[0], v4[1]);
+            pk.y = pack_bf16x2(v4[2], v4[3]);
             *reinterpret_cast<uint2*>(dv_out + t2 * 32 + 8 * g + 4 * h) = pk;
         }
 }
@@ -472,7 +541,7 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dkv_mfma_kerne
 bool attn_mfma_supported(const AttnArgs& a) {
     auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
     if (a.d != 64 && a.d != 128) return false;
-    if (a.S % 128) return false;
+    if (a.S % 64) return false;
     return al16(a.qkv) && al16(a.ctx) && (!a.dctx || al16(a.dctx)) && (!a.dqkv || al16(a.dqkv));
 }
 
@@ -484,7 +553,7 @@ static hipError_t set_smem(K kern, size_t smem) {
 
 hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
     const float scale = 1.f / sqrtf((float)a.d);
-    const dim3 grid(a.S / 128, a.heads, a.B), block(256);
+    const dim3 grid((a.S / 64) * a.heads * a.B), block(256);
     if (a.d == 128) {
         const size_t smem = 2 * 2 * 64 * 128 * 2;
         hipLaunchKernelGGL((attn_fwd_mfma_kernel<128>), grid, block, smem, s, a, scale);
@@ -501,7 +570,7 @@ hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a, a.d);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const dim3 grid(a.S / 128, a.heads, a.B), block(256);
+    const dim3 grid((a.S / 64) * a.heads * a.B), block(256);
     if (a.d == 128) {
         const size_t smem = 2 * 2 * 64 * 128 * 2, smem2 = 2 * (2 * 64 * 128 * 2 + 512);
         static bool set = false;

@@ -145,6 +145,9 @@ ATTN_CASES = [
     (2, 256, 2, 64, False, None),
     (1, 640, 2, 128, False, [333]),
     (2, 1024, 1, 128, True, None),
+    (2, 192, 2, 64, True, None),
+    (1, 320, 3, 128, False, [200]),
+    (2, 64, 2, 128, True, None),
 ]
 
 
