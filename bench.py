@@ -26,12 +26,68 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
 
+def bench_schedule(args, cfg, bp, si, torch, np):
+    """Whole BitPipe iteration (V-shaped bidirectional order, all virtual devices time-sliced on
+    the one GPU): a step is one bp_run_schedule call over all micro-batches."""
+    D = cfg.n_chunks // 2
+    N = cfg.n_micro
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        return torch.from_numpy(si.to_bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+
+    st = bp.bp_stage_init_ex(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, cfg.causal,
+                             n_chunks=cfg.n_chunks, mlp=cfg.mlp, dtype=bp.BP_BF16, ln_eps=cfg.ln_eps)
+    params = si.make_params(cfg)
+    for c in range(cfg.n_chunks):
+        for l in range(cfg.layers):
+            for name, tid in bp.TENSOR_IDS.items():
+                bp.bp_stage_set_param(st, c, l, tid, params[c][l][name])
+    inputs = to_dev(np.stack([si.make_activation(cfg, "act_in", m) for m in range(N)]))
+    targets = to_dev(np.stack([si.make_activation(cfg, "target", m) for m in range(N)]))
+    order = bp.bp_schedule_generate(D, N)
+    for _ in range(args.warmup):
+        bp.bp_run_schedule(st, order, D, inputs, targets)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loss = bp.bp_run_schedule(st, order, D, inputs, targets)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    flops_step = cfg.flops_per_microbatch() * cfg.n_chunks * N
+    tflops = flops_step * args.steps / dt / 1e12
+    bp.bp_prof_enable(st, 1)
+    for _ in range(args.steps):
+        bp.bp_run_schedule(st, order, D, inputs, targets)
+    gm = bp.bp_prof_get(st, bp.KERNEL_IDS["gemm"])
+    bp.bp_prof_enable(st, 0)
+    gemm_tflops = gm["flops"] / max(gm["ms"], 1e-9) / 1e9
+    result = {
+        "metric": "stage fwd+bwd TFLOP/s + MFMA util per micro-batch; tokens/s on 1 GPU",
+        "value": round(tflops, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "stages": cfg.n_chunks, "virtual_devices": D, "layers_per_stage": cfg.layers,
+                   "hidden": cfg.hidden, "heads": cfg.heads, "seq": cfg.seq, "microbatch": cfg.microbatch,
+                   "micro_batches_per_step": N, "order": "V-shaped bidirectional, concatenated units"},
+        "tokens_per_s": round(cfg.T * N * args.steps / dt, 1),
+        "mfma_util": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "loss": round(float(loss), 4),
+        "roofline": {"kernel": "bf16 MFMA GEMM (forward, dgrad, wgrad of the four linear layers)", "bound": "mfma",
+                     "achieved": round(gemm_tflops, 3), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(gemm_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "avg_launch_ms": round(gm["ms"] / max(gm["launches"], 1), 5), "traffic": None},
+    }
+    bp.bp_stage_destroy(st)
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=1, help="index into the baseline configs (1..3)")
+    ap.add_argument("--config", type=int, default=1, help="index into the baseline configs (1..3: stage configs; 4: whole V-schedule iteration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -49,7 +105,8 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     cfg = si.CONFIGS[args.config]
-    assert cfg.n_chunks == 1, "bench.py times single-chunk stage configs"
+    if cfg.n_chunks > 1:
+        return bench_schedule(args, cfg, bp, si, torch, np)
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
 
     def to_dev(a):

@@ -20,6 +20,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;
 
@@ -381,24 +382,56 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
         }
     }
 
-    const int col_l = lane & 31, row_l = 4 * (lane >> 5);
+    // ---- epilogue through LDS.  The accumulators hold one column and 16 scattered rows per
+    // lane; writing them out directly costs one narrow store instruction per element.  Each
+    // wave instead lays 32 rows of its tile out in its own LDS region and reads them back with
+    // 16 bytes per lane, so global stores (and the fp32 read-modify-write of a weight gradient)
+    // are full 16-byte accesses over 256-byte row segments.
+    __syncthreads();                                    // every wave is done reading the stages
+    constexpr int WTN = BN / WN;                        // wave tile width
+    constexpr int PITCH = WTN + 8;                      // floats; 4 rows apart = 32 banks apart
+    float* ep = (float*)smem + wave * (32 * PITCH);
+    const int h = lane >> 5;
+    const int n_base = n0 + wn * WTN;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * (BN / WN) + j * 32 + col_l;
-        const float bias = (!g.accumulate && g.bias) ? g.bias[n] : 0.f;
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-                const size_t o = (size_t)m * g.ldc + n;
-                if (g.accumulate) {
-                    ((float*)g.C)[o] += acc[i][j][v];
-                } else {
-                    float r = acc[i][j][v] + bias;
-                    if (g.residual) r += (float)((const bf16_t*)g.residual)[o];
-                    ((bf16_t*)g.C)[o] = (bf16_t)r;
+            for (int v = 0; v < 16; ++v)
+                ep[(8 * (v >> 2) + 4 * h + (v & 3)) * PITCH + j * 32 + (lane & 31)] = acc[i][j][v];
+        const int m_base = m0 + wm * (BM / WM) + i * 32;
+        if (g.accumulate) {
+            constexpr int LPR = WTN / 4, RPI = 64 / LPR;        // lanes per row, rows per instruction
+            const int col = (lane % LPR) * 4;
+#pragma unroll
+            for (int r = 0; r < 32; r += RPI) {
+                const int row = r + lane / LPR;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * PITCH + col);
+                f32x4* c = reinterpret_cast<f32x4*>((float*)g.C + (size_t)(m_base + row) * g.ldc + n_base + col);
+                *c = *c + v;
+            }
+        } else {
+            constexpr int LPR = WTN / 8, RPI = 64 / LPR;
+            const int col = (lane % LPR) * 8;
+            float bias[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) bias[e] = g.bias ? g.bias[n_base + col + e] : 0.f;
+#pragma unroll
+            for (int r = 0; r < 32; r += RPI) {
+                const int row = r + lane / LPR;
+                const f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * PITCH + col);
+                const f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * PITCH + col + 4);
+                float o[8] = {v0[0] + bias[0], v0[1] + bias[1], v0[2] + bias[2], v0[3] + bias[3],
+                              v1[0] + bias[4], v1[1] + bias[5], v1[2] + bias[6], v1[3] + bias[7]};
+                const size_t off = (size_t)(m_base + row) * g.ldc + n_base + col;
+                if (g.residual) {
+                    float rs[8];
+                    load8((const bf16_t*)g.residual + off, rs);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] += rs[e];
                 }
+                store8((bf16_t*)g.C + off, o);
             }
         }
     }
@@ -434,7 +467,9 @@ template <int BM, int BN, int WM, int WN, int NS>
 static hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
     const int tiles_m = g.M / BM, tiles_n = g.N / BN;
     const dim3 grid(tiles_m * tiles_n), block(WM * WN * 64);
-    const size_t smem = (size_t)NS * (BM + BN) * 64 * 2;
+    const size_t stages = (size_t)NS * (BM + BN) * 64 * 2;
+    const size_t epilogue = (size_t)WM * WN * 32 * (BN / WN + 8) * sizeof(float);
+    const size_t smem = stages > epilogue ? stages : epilogue;
 #define BP_GEMM_LAUNCH(AR, BR)                                                                   \
     do {                                                                                         \
         auto kern = gemm_dma_kernel<BM, BN, WM, WN, 64, NS, AR, BR>;                             \
@@ -466,7 +501,9 @@ bool gemm_mfma_supported(const GemmArgs& g) {
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
-    const bool aligned128 = g.M % 128 == 0 && g.N % 128 == 0 && g.K % BK == 0;
+    auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+    const bool aligned128 = g.M % 128 == 0 && g.N % 128 == 0 && g.K % BK == 0 && g.ldc % 8 == 0 &&
+                            al16(g.C) && (!g.residual || al16(g.residual));
     if (!aligned128) return launch_cfg<128, 128, 2, 2, true>(g, s);
     // 256 x 256 tiles (8 waves) once they fill at least three quarters of the 256 CUs
     const bool aligned256 = g.M % 256 == 0 && g.N % 256 == 0;
