@@ -78,6 +78,8 @@ struct Stage {
     void *ws_big1[2] = {}, *ws_big2[2] = {}, *ws_h1[2] = {}, *ws_h2[2] = {}, *ws_h5[2] = {};
     void *ws_h4 = nullptr, *ws_dx[3] = {};
     float *ws_delta = nullptr, *ws_colsum[2] = {};
+    float* ws_splitk = nullptr;          // split-K partials of main-stream GEMMs: 4 * T * H floats
+    size_t ws_splitk_elems = 0;
 
     // key-padding lengths per micro-batch (device int32 [B])
     std::map<int, int32_t*> lens;

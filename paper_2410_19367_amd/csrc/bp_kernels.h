@@ -22,6 +22,12 @@ struct GemmArgs {
     int lda, ldb, ldc;
     int a_t, b_t;
     int accumulate;          // 1: C is fp32 and receives +=
+    // optional split-K workspace (fp32, split_ws_elems floats).  When given, a GEMM whose output
+    // has too few 256x256 tiles to fill the chip may cut K into slices computed by different
+    // blocks, each writing an fp32 partial there; a second kernel adds the partials in a fixed
+    // order and applies the epilogue.  Null: never split.
+    float* split_ws = nullptr;
+    size_t split_ws_elems = 0;
 };
 
 // picks the MFMA kernel when the shape allows it, else the generic one

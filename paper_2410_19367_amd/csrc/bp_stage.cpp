@@ -190,6 +190,10 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     }
     for (int i = 0; i < 3 && !rc; ++i) rc = dev_alloc(&st->ws_dx[i], TH);
     if (!rc) rc = dev_alloc(&st->ws_h4, TH);
+    if (!rc && st->dtype == BP_BF16) {
+        st->ws_splitk_elems = (size_t)4 * st->T * st->H;
+        rc = dev_alloc((void**)&st->ws_splitk, st->ws_splitk_elems * sizeof(float));
+    }
     if (!rc) rc = dev_alloc((void**)&st->ws_delta, (size_t)st->B * st->heads * st->S * sizeof(float));
     if (rc) { delete st; return rc; }
 
@@ -246,6 +250,7 @@ Stage::~Stage() {
     }
     for (auto b : ws_dx) hipFree(b);
     hipFree(ws_h4);
+    hipFree(ws_splitk);
     hipFree(ws_delta);
     for (auto& kv : lens) hipFree(kv.second);
     hipFree(sched_act); hipFree(sched_grad); hipFree(sched_loss);
@@ -409,6 +414,10 @@ int Stage::gemm(const void* A, int lda, int a_t, const void* Bm, int ldb, int b_
     g.A = A; g.B = Bm; g.C = C; g.bias = bias; g.residual = residual;
     g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
     g.a_t = a_t; g.b_t = b_t; g.accumulate = accumulate;
+    if (!use_on || on == stream) {      // the split-K workspace belongs to the main stream
+        g.split_ws = ws_splitk;
+        g.split_ws_elems = ws_splitk_elems;
+    }
     Scoped sc(this, BP_K_GEMM, 2.0 * M * N * K, 0);
     BP_LAUNCH(launch_gemm(dtype, g, use_on ? on : stream));
     return BP_OK;

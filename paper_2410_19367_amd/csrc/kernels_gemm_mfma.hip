@@ -284,7 +284,7 @@ __device__ __forceinline__ bf16x8 read_frag2(const char* lds, int row0, int kk, 
 }
 
 template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n, int splits) {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2, STAGE = A_BYTES + B_BYTES;
@@ -293,7 +293,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     // tile order: each XCD (blocks are dealt round-robin over 8 XCDs) gets a contiguous range of
     // ids, walked in groups of 4 tile rows so that concurrent blocks share A rows and B columns
     const int nblk = tiles_m * tiles_n;
-    int t = blockIdx.x;
+    const int sp = blockIdx.x / nblk;                    // K slice of this block (0 when not split)
+    int t = blockIdx.x % nblk;
     if (nblk % 8 == 0) t = (t & 7) * (nblk >> 3) + (t >> 3);
     constexpr int GM = 4;
     const int per_group = GM * tiles_n;
@@ -306,8 +307,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction
     const int wm = wave / WN, wn = wave % WN;
 
-    const bf16_t* a_base = A_RMAJOR ? (const bf16_t*)g.A + m0 : (const bf16_t*)g.A + (size_t)m0 * g.lda;
-    const bf16_t* b_base = B_RMAJOR ? (const bf16_t*)g.B + n0 : (const bf16_t*)g.B + (size_t)n0 * g.ldb;
+    const int k_len = g.K / splits;
+    const size_t k_begin = (size_t)sp * k_len;
+    const bf16_t* a_base = A_RMAJOR ? (const bf16_t*)g.A + m0 + k_begin * g.lda
+                                    : (const bf16_t*)g.A + (size_t)m0 * g.lda + k_begin;
+    const bf16_t* b_base = B_RMAJOR ? (const bf16_t*)g.B + n0 + k_begin * g.ldb
+                                    : (const bf16_t*)g.B + (size_t)n0 * g.ldb + k_begin;
     const size_t a_step = A_RMAJOR ? (size_t)BKT * g.lda : BKT;
     const size_t b_step = B_RMAJOR ? (size_t)BKT * g.ldb : BKT;
 
@@ -325,7 +330,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nk = g.K / BKT;
+    const int nk = k_len / BKT;
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) {
         if (s < nk) {
@@ -401,7 +406,17 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
             for (int v = 0; v < 16; ++v)
                 ep[(8 * (v >> 2) + 4 * h + (v & 3)) * PITCH + j * 32 + (lane & 31)] = acc[i][j][v];
         const int m_base = m0 + wm * (BM / WM) + i * 32;
-        if (g.accumulate) {
+        if (splits > 1) {           // fp32 partial of this K slice, row-major [M][N]
+            constexpr int LPR = WTN / 4, RPI = 64 / LPR;
+            const int col = (lane % LPR) * 4;
+            float* slab = g.split_ws + (size_t)sp * g.M * g.N;
+#pragma unroll
+            for (int r = 0; r < 32; r += RPI) {
+                const int row = r + lane / LPR;
+                *reinterpret_cast<f32x4*>(slab + (size_t)(m_base + row) * g.N + n_base + col) =
+                    *reinterpret_cast<const f32x4*>(ep + row * PITCH + col);
+            }
+        } else if (g.accumulate) {
             constexpr int LPR = WTN / 4, RPI = 64 / LPR;        // lanes per row, rows per instruction
             const int col = (lane % LPR) * 4;
 #pragma unroll
@@ -463,10 +478,48 @@ static hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Sum the split-K partials in slice order and apply the epilogue; 8 outputs per thread.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int splits) {
+    const size_t vec = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t total = (size_t)g.M * g.N / 8;
+    if (vec >= total) return;
+    const size_t e0 = vec * 8;
+    const int m = (int)(e0 / g.N), n = (int)(e0 % g.N);
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int sp = 0; sp < splits; ++sp) {
+        float v[8];
+        load8(g.split_ws + (size_t)sp * g.M * g.N + e0, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += v[i];
+    }
+    const size_t off = (size_t)m * g.ldc + n;
+    if (g.accumulate) {
+        float c[8];
+        load8((const float*)g.C + off, c);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) c[i] += acc[i];
+        store8((float*)g.C + off, c);
+    } else {
+        if (g.bias) {
+            float b[8];
+            load8(g.bias + n, b);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] += b[i];
+        }
+        if (g.residual) {
+            float r[8];
+            load8((const bf16_t*)g.residual + off, r);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] += r[i];
+        }
+        store8((bf16_t*)g.C + off, acc);
+    }
+}
+
 template <int BM, int BN, int WM, int WN, int NS>
-static hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
+static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1) {
     const int tiles_m = g.M / BM, tiles_n = g.N / BN;
-    const dim3 grid(tiles_m * tiles_n), block(WM * WN * 64);
+    const dim3 grid(tiles_m * tiles_n * splits), block(WM * WN * 64);
     const size_t stages = (size_t)NS * (BM + BN) * 64 * 2;
     const size_t epilogue = (size_t)WM * WN * 32 * (BN / WN + 8) * sizeof(float);
     const size_t smem = stages > epilogue ? stages : epilogue;
@@ -480,13 +533,17 @@ static hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
             if (e != hipSuccess) return e;                                                       \
             attr_set = true;                                                                     \
         }                                                                                        \
-        hipLaunchKernelGGL(kern, grid, block, smem, s, g, tiles_m, tiles_n);                     \
+        hipLaunchKernelGGL(kern, grid, block, smem, s, g, tiles_m, tiles_n, splits);             \
     } while (0)
     if (!g.a_t && !g.b_t) BP_GEMM_LAUNCH(false, true);
     else if (!g.a_t && g.b_t) BP_GEMM_LAUNCH(false, false);
     else if (g.a_t && !g.b_t) BP_GEMM_LAUNCH(true, true);
     else BP_GEMM_LAUNCH(true, false);
 #undef BP_GEMM_LAUNCH
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits <= 1) return e;
+    const size_t vecs = (size_t)g.M * g.N / 8;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((vecs + 255) / 256)), dim3(256), 0, s, g, splits);
     return hipGetLastError();
 }
 
@@ -507,7 +564,19 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     if (!aligned128) return launch_cfg<128, 128, 2, 2, true>(g, s);
     // 256 x 256 tiles (8 waves) once they fill at least three quarters of the 256 CUs
     const bool aligned256 = g.M % 256 == 0 && g.N % 256 == 0;
-    if (aligned256 && (long)(g.M / 256) * (g.N / 256) >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s);
+    const long t256 = aligned256 ? (long)(g.M / 256) * (g.N / 256) : 0;
+    if (t256 >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s);
+    // Few output tiles but a long K: 256x256 tiles on K slices keep the operand traffic per flop
+    // at the large-tile level (128x128 tiles are bound by the per-CU load path) and still give
+    // every CU a block.  Slices stay >= 1024 deep so the partial traffic remains small.
+    if (t256 > 0 && g.split_ws) {
+        int splits = (int)(256 / t256);
+        if (splits > 4) splits = 4;
+        while (splits > 1 && (g.K % (splits * BK) || g.K / splits < 1024 ||
+                              (size_t)splits * g.M * g.N > g.split_ws_elems))
+            --splits;
+        if (splits > 1 && t256 * splits >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s, splits);
+    }
     return launch_dma<128, 128, 2, 2, 2>(g, s);
 }
 
