@@ -97,7 +97,9 @@ int bp_stage_set_param(bp_stage_t* st, int chunk, int layer, int tensor_id,
 int bp_stage_get_grad(bp_stage_t* st, int chunk, int layer, int tensor_id,
                       float* host_f32, size_t n);
 
-/* Zero all gradient accumulators (the flush between iterations, Section 2).  Asynchronous. */
+/* Zero all gradient accumulators (the flush between iterations, Section 2).  Launches nothing:
+ * the accumulators are marked clear and the first backward of each layer after this call writes
+ * its gradient instead of adding it; backward calls already enqueued are not affected. */
 int bp_stage_zero_grad(bp_stage_t* st);
 
 /* BERT-style key padding: valid lengths (host int32 [microbatch], each in 1..seq) used by the

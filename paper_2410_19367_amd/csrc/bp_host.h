@@ -63,6 +63,10 @@ struct Stage {
     // parameters (matrices in the storage dtype, vectors fp32) and fp32 gradients per direction
     void* params = nullptr;
     float* grads[2] = {nullptr, nullptr};
+    // per (direction, chunk, layer): 1 while the layer's gradients are logically zero.  The buffer
+    // contents are then undefined and the next backward overwrites them instead of adding, which
+    // saves both the clearing pass and the first read of every read-modify-write.
+    std::vector<uint8_t> grad_clean[2];
     // Each weight matrix is also kept transposed ([out,in]) so that the forward GEMMs read both
     // operands contraction-major like the data-gradient GEMMs do; slots BP_N_TENSORS.. hold them.
     size_t p_off[BP_N_TENSORS + 4], g_off[BP_N_TENSORS], p_layer_bytes = 0, g_layer_bytes = 0;

@@ -21,7 +21,7 @@ struct GemmArgs {
     int M, N, K;
     int lda, ldb, ldc;
     int a_t, b_t;
-    int accumulate;          // 1: C is fp32 and receives +=
+    int accumulate;          // 1: C is fp32 and receives +=;  2: C is fp32 and is overwritten (= instead of +=)
     // optional split-K workspace (fp32, split_ws_elems floats).  When given, a GEMM whose output
     // has too few 256x256 tiles to fill the chip may cut K into slices computed by different
     // blocks, each writing an fp32 partial there; a second kernel adds the partials in a fixed
@@ -69,6 +69,7 @@ constexpr int kMaxColsumJobs = 8;
 struct ColsumBatch {
     ColsumJob jobs[kMaxColsumJobs];
     int n;
+    int overwrite = 0;       // 1: outputs receive = instead of +=
 };
 hipError_t launch_colsum_batch(int dtype, int T, const ColsumBatch& batch, hipStream_t stream);
 

@@ -213,6 +213,8 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     hipError_t e = hipMemsetAsync(st->params, 0, n_layers * poff, st->stream);
     if (e == hipSuccess) e = launch_fill_f32(st->grads[0], n_layers * goff / 4, 0.f, st->stream);
     if (e == hipSuccess) e = launch_fill_f32(st->grads[1], n_layers * goff / 4, 0.f, st->stream);
+    st->grad_clean[0].assign(n_layers, 1);
+    st->grad_clean[1].assign(n_layers, 1);
     for (int c = 0; c < st->n_chunks && e == hipSuccess; ++c)
         for (int l = 0; l < st->L && e == hipSuccess; ++l) {
             e = launch_fill_f32((float*)st->param(c, l, BP_LN1_G), st->H, 1.f, st->stream);
@@ -312,6 +314,10 @@ int Stage::get_grad(int chunk, int layer, int id, float* host, size_t n) {
     if (rc) return rc;
     if (!host) return fail(BP_EINVAL, "host pointer is null");
     if ((rc = sync_all())) return rc;
+    if (grad_clean[0][(size_t)chunk * L + layer]) {     // nothing accumulated since the last clear
+        memset(host, 0, n * sizeof(float));
+        return BP_OK;
+    }
     hipError_t e = hipMemcpyAsync(host, grad(0, chunk, layer, id), n * sizeof(float),
                                   hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
@@ -320,23 +326,29 @@ int Stage::get_grad(int chunk, int layer, int id, float* host, size_t n) {
 }
 
 int Stage::zero_grad() {
-    const size_t n = (size_t)n_chunks * L * g_layer_bytes / sizeof(float);
-    Scoped sc(this, BP_K_OTHER, 0, 0);
-    // every writer of the gradient buffers runs on the side stream, so the clear goes there too
-    hipStream_t gs = side_stream();
-    hipError_t e = launch_fill_f32(grads[0], n, 0.f, gs);
-    if (e == hipSuccess) e = launch_fill_f32(grads[1], n, 0.f, gs);
-    if (e != hipSuccess) return fail(BP_EHIP, "zero_grad: %s", hipGetErrorString(e));
+    // host bookkeeping only: kernels enqueued before this call still add into the old contents,
+    // kernels enqueued after it see the layer as clear and overwrite
+    grad_clean[0].assign(grad_clean[0].size(), 1);
+    grad_clean[1].assign(grad_clean[1].size(), 1);
     return BP_OK;
 }
 
 int Stage::merge_directions() {
-    const size_t n = (size_t)n_chunks * L * g_layer_bytes / sizeof(float);
+    const size_t n = g_layer_bytes / sizeof(float);
     Scoped sc(this, BP_K_OTHER, 0, 0);
+    // every writer of the gradient buffers runs on the side stream, so the merge goes there too
     hipStream_t gs = side_stream();
-    hipError_t e = launch_add_f32(grads[0], grads[1], n, gs);
-    if (e == hipSuccess) e = launch_fill_f32(grads[1], n, 0.f, gs);
-    if (e != hipSuccess) return fail(BP_EHIP, "merge_directions: %s", hipGetErrorString(e));
+    for (size_t i = 0; i < grad_clean[0].size(); ++i) {
+        if (grad_clean[1][i]) continue;
+        float* g0 = (float*)((char*)grads[0] + i * g_layer_bytes);
+        float* g1 = (float*)((char*)grads[1] + i * g_layer_bytes);
+        hipError_t e = grad_clean[0][i]
+                           ? hipMemcpyAsync(g0, g1, g_layer_bytes, hipMemcpyDeviceToDevice, gs)
+                           : launch_add_f32(g0, g1, n, gs);
+        if (e != hipSuccess) return fail(BP_EHIP, "merge_directions: %s", hipGetErrorString(e));
+        grad_clean[0][i] = 0;
+        grad_clean[1][i] = 1;
+    }
     return BP_OK;
 }
 
@@ -517,6 +529,8 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         char* sb = (char*)slots[slot].buf + (size_t)l * s_layer_bytes;
         auto P = [&](int id) { return param(chunk, l, id); };
         auto G = [&](int id) { return grad(dir, chunk, l, id); };
+        uint8_t& clean = grad_clean[dir][(size_t)chunk * L + l];
+        const int acc = clean ? 2 : 1;          // first contribution after a clear overwrites
         void* dx = l == 0 ? grad_in : ws_dx[l % 3];
         void *big1 = ws_big1[p], *big2 = ws_big2[p], *h1 = ws_h1[p], *h2 = ws_h2[p], *h5 = ws_h5[p];
         if (two && layer_done_pending[p]) {     // workspaces of this parity still read by the side stream?
@@ -534,7 +548,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
 
         // z = y + g W2 + b2
         BP_HIP(hand_over(0));                                                                               // dz
-        if ((rc = gemm(sb + s_g, F, 1, dz, H, 0, G(BP_W2), H, F, H, T, nullptr, nullptr, 1, ss, true))) return rc;   // dW2
+        if ((rc = gemm(sb + s_g, F, 1, dz, H, 0, G(BP_W2), H, F, H, T, nullptr, nullptr, acc, ss, true))) return rc;   // dW2
         if ((rc = gemm(dz, H, 0, P(BP_W2), H, 1, big1, F, T, F, H, nullptr, nullptr, 0))) return rc;        // dg
         {   // du = dg * gelu'(u + b1); db1 partials (folded with the other column sums below)
             Scoped sc(this, BP_K_GELU_BWD, 0, 3.0 * T * F * esz);
@@ -542,7 +556,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
                                       stream));
         }
         BP_HIP(hand_over(1));                                                                               // du
-        if ((rc = gemm(sb + s_m, H, 1, big1, F, 0, G(BP_W1), F, H, F, T, nullptr, nullptr, 1, ss, true))) return rc;  // dW1
+        if ((rc = gemm(sb + s_m, H, 1, big1, F, 0, G(BP_W1), F, H, F, T, nullptr, nullptr, acc, ss, true))) return rc;  // dW1
         if ((rc = gemm(big1, F, 0, P(BP_W1), F, 1, h1, H, T, H, F, nullptr, nullptr, 0))) return rc;        // dm
         {   // dy = dz + LN2bwd(dm)
             Scoped sc(this, BP_K_LN_BWD, 0, 4 * unit);
@@ -551,7 +565,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         }
         // y = x + ctx Wo + bo
         BP_HIP(hand_over(2));                                                                               // dy
-        if ((rc = gemm(sb + s_ctx, H, 1, h2, H, 0, G(BP_WO), H, H, H, T, nullptr, nullptr, 1, ss, true))) return rc;  // dWo
+        if ((rc = gemm(sb + s_ctx, H, 1, h2, H, 0, G(BP_WO), H, H, H, T, nullptr, nullptr, acc, ss, true))) return rc;  // dWo
         if ((rc = gemm(h2, H, 0, P(BP_WO), H, 1, ws_h4, H, T, H, H, nullptr, nullptr, 0))) return rc;       // dctx
         {
             AttnArgs a{B, S, heads, d, causal ? 1 : 0, ln, sb + s_qkv, sb + s_ctx, (float*)(sb + s_lse),
@@ -561,13 +575,14 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         }
         // qkv = a Wqkv + bqkv
         BP_HIP(hand_over(3));                                                                               // dqkv
-        if ((rc = gemm(sb + s_a, H, 1, big2, 3 * H, 0, G(BP_WQKV), 3 * H, H, 3 * H, T, nullptr, nullptr, 1, ss, true)))
+        if ((rc = gemm(sb + s_a, H, 1, big2, 3 * H, 0, G(BP_WQKV), 3 * H, H, 3 * H, T, nullptr, nullptr, acc, ss, true)))
             return rc;
         if ((rc = gemm(big2, 3 * H, 0, P(BP_WQKV), 3 * H, 1, h5, H, T, H, 3 * H, nullptr, nullptr, 0))) return rc;  // da
         BP_HIP(hand_over(4));                                                                               // da
         {   // every bias and LayerNorm-parameter gradient of the layer in one batched reduction
             ColsumBatch cb;
             cb.n = 6;
+            cb.overwrite = clean ? 1 : 0;
             cb.jobs[0] = ColsumJob{dz, nullptr, nullptr, nullptr, H, G(BP_B2), nullptr, p_b2};
             cb.jobs[1] = ColsumJob{h1, sb + s_y, (const float*)(sb + s_mean2), (const float*)(sb + s_rstd2), H,
                                    G(BP_LN2_B), G(BP_LN2_G), p_ln2};
@@ -579,6 +594,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
             Scoped sc(this, BP_K_COLSUM, 0, 0);
             BP_LAUNCH(launch_colsum_batch(dtype, T, cb, ss));
         }
+        clean = 0;
         if (two) {
             BP_HIP(hipEventRecord(ev_layer_done[p], ss));
             layer_done_pending[p] = true;

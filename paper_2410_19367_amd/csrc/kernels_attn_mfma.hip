@@ -30,6 +30,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+// bare v_exp_f32: arguments here are <= 8 and anything below -126 may flush to zero
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // ---- tile layout: [rows][D] bf16, 16-byte chunks XOR-swizzled by row
 template <int D> __device__ __forceinline__ int swz(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3))
@@ -182,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
         float mx = -INFINITY;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            float sv_ = st2[v] * c;
+            float sv_ = st2[v];
             if (need_mask) {
                 const int key = kw + acc_row(v, h);
                 if ((a.causal && key > q_lane) || key >= klen) sv_ = -INFINITY;
@@ -190,24 +193,30 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
             st2[v] = sv_;
             mx = fmaxf(mx, sv_);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m, mx);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;     // c > 0: the maximum commutes with the scaling
+        // The reference point m of the running softmax only has to stay within a bounded distance of
+        // the true maximum: it moves (and O, l are rescaled) only when some query of the wave sees a
+        // score more than 8 binary orders above it, so p <= 2^8 and most tiles skip the rescaling.
+        if (__builtin_amdgcn_ballot_w64(mx > m + 8.f) != 0) {
+            const float m_new = fmaxf(m, mx);
+            const float alpha = m == -INFINITY ? 0.f : fast_exp2(m - m_new);
+            m = m_new;
+            lsum *= alpha;
+#pragma unroll
+            for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) ot[t2][v] *= alpha;
+        }
         // a row whose keys are all masked so far keeps m = -inf; avoid inf - inf
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = exp2f(m - m_use);
-        m = m_new;
+        const float m_use = m == -INFINITY ? 0.f : m;
         float ps = 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const float p = exp2f(st2[v] - m_use);
+            const float p = fast_exp2(__builtin_fmaf(st2[v], c, -m_use));
             st2[v] = p;
             ps += p;
         }
-        lsum = lsum * alpha + ps;
-#pragma unroll
-        for (int t2 = 0; t2 < DT; ++t2)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) ot[t2][v] *= alpha;
+        lsum += ps;
         // O^T (D x 32 queries) += V^T P^T over this wave's 32 keys
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
@@ -235,7 +244,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
     if (kh == 1) return;
     const float m1 = xo[DT * 16 * 64 + lane], l1 = xo[DT * 16 * 64 + 64 + lane];
     const float mm = fmaxf(m, m1);                      // finite: key 0 (or any valid key) is in half 0 or 1
-    const float a0 = exp2f(m - mm), a1 = exp2f(m1 - mm);
+    const float a0 = fast_exp2(m - mm), a1 = fast_exp2(m1 - mm);
     l = l * a0 + l1 * a1;
     const float inv = 1.f / l;
     bf16_t* out = (bf16_t*)a.ctx + ((size_t)b * a.S + q_lane) * H + head * D;
@@ -352,7 +361,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            float p = exp2f(sacc[v] * c - lse2);
+            float p = fast_exp2(__builtin_fmaf(sacc[v], c, -lse2));
             if (need_mask) {
                 const int key = kw + acc_row(v, h);
                 if ((a.causal && key > q_lane) || key >= klen) p = 0.f;
@@ -485,7 +494,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int qi = acc_row(v, h);
-            float p = exp2f(sacc[v] * c - s_lse[qi]);
+            float p = fast_exp2(__builtin_fmaf(sacc[v], c, -s_lse[qi]));
             if (need_mask && k_lane > qw + qi) p = 0.f;
             if (k_lane >= klen) p = 0.f;
             sacc[v] = p;                                 // P

@@ -203,7 +203,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(GemmArgs g, int 
                 if (RAGGED && m >= g.M) continue;
                 const size_t o = (size_t)m * g.ldc + n;
                 if (g.accumulate) {
-                    ((float*)g.C)[o] += acc[i][j][v];
+                    float* c = (float*)g.C + o;
+                    *c = g.accumulate == 2 ? acc[i][j][v] : *c + acc[i][j][v];
                 } else {
                     float r = acc[i][j][v] + bias;
                     if (g.residual) r += (float)((const bf16_t*)g.residual)[o];
@@ -424,7 +425,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
                 const int row = r + lane / LPR;
                 const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * PITCH + col);
                 f32x4* c = reinterpret_cast<f32x4*>((float*)g.C + (size_t)(m_base + row) * g.ldc + n_base + col);
-                *c = *c + v;
+                if (g.accumulate == 2) *c = v;      // first contribution after a clear: no read
+                else *c = *c + v;
             }
         } else {
             constexpr int LPR = WTN / 8, RPI = 64 / LPR;
@@ -493,7 +495,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int spli
         for (int i = 0; i < 8; ++i) acc[i] += v[i];
     }
     const size_t off = (size_t)m * g.ldc + n;
-    if (g.accumulate) {
+    if (g.accumulate == 2) {
+        store8((float*)g.C + off, acc);
+    } else if (g.accumulate) {
         float c[8];
         load8((const float*)g.C + off, c);
 #pragma unroll

@@ -60,7 +60,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g) {
             float v = acc[i][j];
             const size_t o = (size_t)m * g.ldc + n;
             if (g.accumulate) {
-                ((float*)g.C)[o] += v;
+                float* c = (float*)g.C + o;
+                *c = g.accumulate == 2 ? v : *c + v;
             } else {
                 if (g.bias) v += g.bias[n];
                 if (g.residual) v += to_float<T>(((const T*)g.residual)[o]);

@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void ln_bwd_rows_kernel(const T* __restrict__ 
 // depend on scheduling.
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(ColsumBatch batch, int rows) {
-    __shared__ float red[2][4][512];
+    __shared__ float red[2][4][576];
     const ColsumJob job = batch.jobs[blockIdx.z];
     const int N = job.N;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -134,34 +134,40 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(ColsumBatch batch, 
     const int r1 = min(r0 + kColsumRows, rows);
     float sa[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (col < N) {
-        constexpr int RPW = kColsumRows / 4;
-        float a[RPW][8], xv[RPW][8];
+        // a wave's 8 rows in two groups of 4: all loads of a group are in flight together, and the
+        // register footprint stays small enough for every block of the launch to be resident
+        constexpr int RPW = kColsumRows / 4, GRP = 4;
 #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const int r = r0 + w + 4 * j;
-            if (r < r1) {
-                load8(A + (size_t)r * N + col, a[j]);
-                if (with_x) load8(X + (size_t)r * N + col, xv[j]);
-            }
-        }
+        for (int j0 = 0; j0 < RPW; j0 += GRP) {
+            float a[GRP][8], xv[GRP][8];
 #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const int r = r0 + w + 4 * j;
-            if (r < r1) {
-                if (with_x) {
-                    const float mu = job.mean[r], rs = job.rstd[r];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) sx[i] += a[j][i] * (xv[j][i] - mu) * rs;
+            for (int j = 0; j < GRP; ++j) {
+                const int r = r0 + w + 4 * (j0 + j);
+                if (r < r1) {
+                    load8(A + (size_t)r * N + col, a[j]);
+                    if (with_x) load8(X + (size_t)r * N + col, xv[j]);
                 }
+            }
 #pragma unroll
-                for (int i = 0; i < 8; ++i) sa[i] += a[j][i];
+            for (int j = 0; j < GRP; ++j) {
+                const int r = r0 + w + 4 * (j0 + j);
+                if (r < r1) {
+                    if (with_x) {
+                        const float mu = job.mean[r], rs = job.rstd[r];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) sx[i] += a[j][i] * (xv[j][i] - mu) * rs;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) sa[i] += a[j][i];
+                }
             }
         }
     }
+    // lane-major with a pitch of 9 floats: conflict-free for the writes and for the reads below
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        red[0][w][lane * 8 + i] = sa[i];
-        red[1][w][lane * 8 + i] = sx[i];
+        red[0][w][lane * 9 + i] = sa[i];
+        red[1][w][lane * 9 + i] = sx[i];
     }
     __syncthreads();
     const int nout = with_x ? 2 : 1;
@@ -169,13 +175,14 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(ColsumBatch batch, 
         const int o = e / 512, c = e % 512;
         const int gc = blockIdx.x * 512 + c;
         if (gc < N) {
-            const float v = (red[o][0][c] + red[o][1][c]) + (red[o][2][c] + red[o][3][c]);
+            const int a = (c >> 3) * 9 + (c & 7);
+            const float v = (red[o][0][a] + red[o][1][a]) + (red[o][2][a] + red[o][3][a]);
             job.part[((size_t)blockIdx.y * nout + o) * N + gc] = v;
         }
     }
 }
 
-// out_k[c] += sum over chunks of part[chunk][k][c].  Block = 64 columns x 4 chunk slices.
+// out_k[c] += (or =, for a batch marked overwrite) sum over chunks of part[chunk][k][c].  Block = 64 columns x 4 chunk slices.
 __global__ __launch_bounds__(256) void colsum_final_kernel(ColsumBatch batch, int chunks) {
     __shared__ float red[4][64];
     const ColsumJob job = batch.jobs[blockIdx.y];
@@ -194,7 +201,8 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(ColsumBatch batch, in
         __syncthreads();
         if (slice == 0 && c < N) {
             float* out = o == 0 ? job.out_a : job.out_ax;
-            out[c] += (red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl]);
+            const float v = (red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl]);
+            out[c] = batch.overwrite ? v : out[c] + v;
         }
         __syncthreads();
     }
@@ -234,7 +242,7 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* dg,   // may ali
                                                        const float* __restrict__ bias,
                                                        T* du, float* __restrict__ part,
                                                        int rows, int F) {
-    __shared__ float red[4][512];
+    __shared__ float red[4][576];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int col = blockIdx.x * 512 + lane * 8;
     const int r0 = blockIdx.y * kColsumRows;
@@ -243,41 +251,45 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* dg,   // may ali
     if (col < F) {
         float b[8];
         load8(bias + col, b);
-        constexpr int RPW = kColsumRows / 4;
-        float a[RPW][8], d[RPW][8];
+        constexpr int RPW = kColsumRows / 4, GRP = 4;
 #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const int r = r0 + w + 4 * j;
-            if (r < r1) {
-                load8(u + (size_t)r * F + col, a[j]);
-                load8(dg + (size_t)r * F + col, d[j]);
-            }
-        }
+        for (int j0 = 0; j0 < RPW; j0 += GRP) {
+            float a[GRP][8], d[GRP][8];
 #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const int r = r0 + w + 4 * j;
-            if (r < r1) {
-                float o[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float x = a[j][i] + b[i];
-                    const float t = gelu_tanh_part(x);
-                    const float dudx = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
-                    const float gp = 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * dudx;
-                    o[i] = d[j][i] * gp;
-                    acc[i] += o[i];
+            for (int j = 0; j < GRP; ++j) {
+                const int r = r0 + w + 4 * (j0 + j);
+                if (r < r1) {
+                    load8(u + (size_t)r * F + col, a[j]);
+                    load8(dg + (size_t)r * F + col, d[j]);
                 }
-                store8(du + (size_t)r * F + col, o);
+            }
+#pragma unroll
+            for (int j = 0; j < GRP; ++j) {
+                const int r = r0 + w + 4 * (j0 + j);
+                if (r < r1) {
+                    float o[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float x = a[j][i] + b[i];
+                        const float t = gelu_tanh_part(x);
+                        const float dudx = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
+                        const float gp = 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * dudx;
+                        o[i] = d[j][i] * gp;
+                        acc[i] += o[i];
+                    }
+                    store8(du + (size_t)r * F + col, o);
+                }
             }
         }
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) red[w][lane * 8 + i] = acc[i];
+    for (int i = 0; i < 8; ++i) red[w][lane * 9 + i] = acc[i];
     __syncthreads();
     for (int c = threadIdx.x; c < 512; c += 256) {
         const int gc = blockIdx.x * 512 + c;
+        const int a = (c >> 3) * 9 + (c & 7);
         if (gc < F)
-            part[(size_t)blockIdx.y * F + gc] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+            part[(size_t)blockIdx.y * F + gc] = (red[0][a] + red[1][a]) + (red[2][a] + red[3][a]);
     }
 }
 

@@ -194,3 +194,42 @@ def test_attention_fwd_bwd(B, S, heads, d, causal, lens, dtype):
     for name, sl in (("dq", slice(0, H)), ("dk", slice(H, 2 * H)), ("dv", slice(2 * H, 3 * H))):
         err = hz.rel_err(got[..., sl], dqkv_ref[..., sl])
         assert err <= (2e-2 if dtype == "bf16" else 5e-5), (name, err)
+
+
+@pytest.mark.parametrize("B,S,heads,d,causal", [(1, 512, 2, 128, True), (2, 256, 2, 64, False), (1, 1024, 1, 128, True)])
+def test_attention_wide_score_range(B, S, heads, d, causal):
+    """Scores whose magnitude grows along the key axis (std up to ~16, maxima tens of binary orders
+    apart between tiles): the running softmax reference has to move many times, by large and by
+    small amounts, and the result must still match the definition."""
+    import torch
+    import paper_2410_19367_amd as bp
+    H = heads * d
+    qkv = _randn("wqkv", (B, S, 3 * H), 1.0, dtype="f32").astype(np.float64)
+    ramp = 1.0 + 7.0 * np.arange(S) / S
+    qkv[..., :H] *= 2.0
+    qkv[..., H:2 * H] *= ramp[None, :, None]
+    qkv = si.round_to(qkv, "bf16")
+    dctx = _randn("wdctx", (B, S, H), dtype="bf16")
+    q64 = qkv.astype(np.float64)
+    q = O._split_heads(q64[..., :H], heads); k = O._split_heads(q64[..., H:2 * H], heads)
+    v = O._split_heads(q64[..., 2 * H:], heads)
+    ctx_h, p = O.attention_fwd(q, k, v, causal, None)
+    ctx_ref = O._merge_heads(ctx_h)
+    dq, dk, dv = O.attention_bwd(O._split_heads(dctx.astype(np.float64), heads), q, k, v, p)
+    dqkv_ref = np.concatenate([O._merge_heads(dq), O._merge_heads(dk), O._merge_heads(dv)], -1)
+    qd = hz.to_dev(qkv, "bf16")
+    ctx = hz.empty_like_dev((B, S, H), "bf16")
+    lse = torch.empty((B, heads, S), device="cuda")
+    bp.bp_op_attention_fwd(bp.BP_BF16, B, S, heads, d, causal, None, qd, ctx, lse)
+    dqkv = hz.empty_like_dev((B, S, 3 * H), "bf16")
+    delta = torch.empty((B, heads, S), device="cuda")
+    ctx_in = hz.to_dev(si.round_to(ctx_ref, "bf16"), "bf16")
+    bp.bp_op_attention_bwd(bp.BP_BF16, B, S, heads, d, causal, None, qd, ctx_in, lse, hz.to_dev(dctx, "bf16"), dqkv,
+                           delta)
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(hz.to_host(ctx)))
+    assert hz.rel_err(hz.to_host(ctx), ctx_ref) <= 1e-2
+    got = hz.to_host(dqkv)
+    for name, sl in (("dq", slice(0, H)), ("dk", slice(H, 2 * H)), ("dv", slice(2 * H, 3 * H))):
+        err = hz.rel_err(got[..., sl], dqkv_ref[..., sl])
+        assert err <= 2e-2, (name, err)

@@ -64,3 +64,38 @@ def test_state_errors():
     with pytest.raises(bp.BitPipeError) as e:
         bp.bp_stage_init(1, 100, 3, 8, 1, 1)
     assert e.value.code == bp.BP_ESHAPE
+
+
+def test_zero_grad_semantics_across_iterations():
+    """The clear between iterations: gradients read right after it are zero, an iteration after it
+    reproduces the oracle's single-iteration gradients (nothing left over from the iteration
+    before, nothing lost from the first micro-batch), and a second chunk that never ran a
+    backward reads as zero."""
+    cfg = si.scaled(si.CONFIGS[1], name="small_clear", layers=2, hidden=256, heads=2, seq=128,
+                    microbatch=2, n_micro=3, n_chunks=2)
+    params = si.make_params(cfg, 3, 0.1)
+    orc = hz.make_oracle(cfg, params)
+    with hz.GpuStage(cfg) as g:
+        g.load_params(params)
+
+        def iteration(seed, with_oracle):
+            for mb in range(cfg.n_micro):
+                x = si.make_activation(cfg, "act_in", mb, seed)
+                go = si.make_activation(cfg, "grad_out", mb, seed)
+                g.forward(0, mb, hz.to_dev(x, cfg.dtype))
+                g.backward(0, mb, hz.to_dev(go, cfg.dtype))
+                if with_oracle:
+                    orc.forward(0, mb, x)
+                    orc.backward(0, mb, go)
+
+        iteration(11, False)                    # leaves non-zero gradients behind
+        assert np.abs(g.grad(0, 1, "w1")).max() > 0
+        g.bp.bp_stage_zero_grad(g.h)
+        for name in si.PARAM_NAMES:
+            assert not g.grad(0, 0, name).any(), name
+        iteration(12, True)
+        for l in range(cfg.layers):
+            for name in si.PARAM_NAMES:
+                err = hz.rel_err(g.grad(0, l, name), orc.get_grad(0, l, name))
+                assert err <= hz.TOL[cfg.dtype], (l, name, err)
+                assert not g.grad(1, l, name).any(), ("chunk 1 never ran", l, name)
