@@ -67,6 +67,13 @@ typedef struct bp_opts {
     int max_inflight;   /* most (chunk, micro-batch) stashes alive at once; 0 -> 8           */
     float ln_eps;       /* 0 -> 1e-5                                                          */
     void* hip_stream;   /* hipStream_t to enqueue on; NULL -> the default stream             */
+    int wgrad_group;    /* weight gradients of this many consecutive backward calls of a chunk
+                           and direction are computed together (one pass over the fp32
+                           accumulator instead of one per micro-batch); 1: each call computes
+                           its own; 2..4; 0 -> min(4, max(1, 8192 / (microbatch*seq))).  A
+                           group keeps the stashes of its waiting micro-batches (beyond
+                           max_inflight) plus their output gradients until it is complete or
+                           until bp_stage_get_grad / bp_run_schedule's merge flushes it.      */
 } bp_opts;
 
 /* Create a stage object holding one chunk of `layers` pre-LN transformer layers in bf16 with
@@ -207,6 +214,14 @@ int bp_prof_get(bp_stage_t* st, int kernel_id, double* total_ms, long long* laun
 int bp_op_gemm(int dtype, int a_t, int b_t, int M, int N, int K,
                const void* A, int lda, const void* B, int ldb, void* C, int ldc,
                const float* bias, const void* residual, int accumulate, void* stream);
+
+/* Weight gradient of a linear map over a group of n micro-batches (1 <= n <= 4) in one pass over
+ * the fp32 accumulator: dW (+)= sum_i X[i]^T dY[i], the synchronous gradient accumulation of
+ * Section 2 with the sum over micro-batches moved inside the contraction.
+ * X: host array of n device pointers, each [T, M] row-major in `dtype`; dY: likewise [T, N];
+ * dW: dev fp32 [M, N].  overwrite != 0: dW = instead of dW +=.  Asynchronous on `stream`. */
+int bp_op_wgrad_group(int dtype, int M, int N, int T, int n, const void* const* X,
+                      const void* const* dY, float* dW, int overwrite, void* stream);
 
 /* out = LN(x) over rows of [T,H]; writes mean and rstd (fp32 [T]). */
 int bp_op_layernorm_fwd(int dtype, int T, int H, const void* x, const float* gamma,

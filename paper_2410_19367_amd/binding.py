@@ -27,7 +27,7 @@ EXPORTS = (
     "bp_stage_get_grad", "bp_stage_zero_grad", "bp_stage_set_seqlens", "bp_stage_forward",
     "bp_stage_backward", "bp_stage_backward_dir", "bp_schedule_vmap", "bp_schedule_generate",
     "bp_schedule_validate", "bp_schedule_simulate", "bp_run_schedule", "bp_prof_enable",
-    "bp_prof_get", "bp_op_gemm", "bp_op_layernorm_fwd", "bp_op_layernorm_bwd",
+    "bp_prof_get", "bp_op_gemm", "bp_op_wgrad_group", "bp_op_layernorm_fwd", "bp_op_layernorm_bwd",
     "bp_op_bias_gelu_fwd", "bp_op_bias_gelu_bwd", "bp_op_colsum_workspace",
     "bp_op_attention_fwd", "bp_op_attention_bwd", "bp_last_error", "bp_version",
 )
@@ -35,7 +35,8 @@ EXPORTS = (
 
 class bp_opts(C.Structure):
     _fields_ = [("n_chunks", C.c_int), ("mlp", C.c_int), ("dtype", C.c_int),
-                ("max_inflight", C.c_int), ("ln_eps", C.c_float), ("hip_stream", C.c_void_p)]
+                ("max_inflight", C.c_int), ("ln_eps", C.c_float), ("hip_stream", C.c_void_p),
+                ("wgrad_group", C.c_int)]
 
 
 class bp_op(C.Structure):
@@ -81,6 +82,7 @@ def lib():
         l.bp_prof_get.argtypes = [vp, ci, C.POINTER(C.c_double), C.POINTER(C.c_longlong),
                                   C.POINTER(C.c_double), C.POINTER(C.c_double)]
         l.bp_op_gemm.argtypes = [ci, ci, ci, ci, ci, ci, vp, ci, vp, ci, vp, ci, vp, vp, ci, vp]
+        l.bp_op_wgrad_group.argtypes = [ci, ci, ci, ci, ci, C.POINTER(vp), C.POINTER(vp), vp, ci, vp]
         l.bp_op_layernorm_fwd.argtypes = [ci, ci, ci, vp, vp, vp, cf, vp, vp, vp, vp]
         l.bp_op_layernorm_bwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         l.bp_op_bias_gelu_fwd.argtypes = [ci, ci, ci, vp, vp, vp, vp]
@@ -129,9 +131,9 @@ def bp_stage_init(layers, hidden, heads, seq, microbatch, causal):
 
 
 def bp_stage_init_ex(layers, hidden, heads, seq, microbatch, causal, n_chunks=0, mlp=0,
-                     dtype=BP_BF16, max_inflight=0, ln_eps=0.0, hip_stream=None):
+                     dtype=BP_BF16, max_inflight=0, ln_eps=0.0, hip_stream=None, wgrad_group=0):
     h = C.c_void_p()
-    o = bp_opts(n_chunks, mlp, dtype, max_inflight, ln_eps, hip_stream)
+    o = bp_opts(n_chunks, mlp, dtype, max_inflight, ln_eps, hip_stream, wgrad_group)
     _check(lib().bp_stage_init_ex(C.byref(h), layers, hidden, heads, seq, microbatch, int(causal),
                                   C.byref(o)))
     return h
@@ -238,6 +240,13 @@ def bp_op_gemm(dtype, a_t, b_t, M, N, K, A, lda, B, ldb, Cm, ldc, bias=None, res
                accumulate=0, stream=None):
     return _check(lib().bp_op_gemm(dtype, a_t, b_t, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cm), ldc,
                                    _ptr(bias), _ptr(residual), accumulate, stream))
+
+
+def bp_op_wgrad_group(dtype, M, N, T, X, dY, dW, overwrite=0, stream=None):
+    n = len(X)
+    xs = (C.c_void_p * n)(*[_ptr(x) for x in X])
+    ys = (C.c_void_p * n)(*[_ptr(y) for y in dY])
+    return _check(lib().bp_op_wgrad_group(dtype, M, N, T, n, xs, ys, _ptr(dW), overwrite, stream))
 
 
 def bp_op_layernorm_fwd(dtype, T, H, x, gamma, beta, eps, out, mean, rstd, stream=None):

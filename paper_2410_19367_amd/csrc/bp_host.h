@@ -40,7 +40,14 @@ struct StashSlot {
     int chunk = -1, mb = -1;
     hipEvent_t side_done = nullptr;   // last side-stream reader of this slot (null: none pending)
     bool side_pending = false;
+    bool held = false;     // backward done, but the weight gradients of its group are still to come
 };
+
+// A micro-batch whose backward has run but whose weight-gradient GEMMs wait for the rest of its
+// group: its stash slot stays held and `buf` keeps, per layer, the gradients w.r.t. the outputs
+// of the four linear maps (dz, du, dy, dqkv).
+struct PendingMb { int slot; void* buf; };
+struct PendGroup { std::vector<PendingMb> items; };
 
 struct Stage {
     // shape
@@ -63,10 +70,17 @@ struct Stage {
     // parameters (matrices in the storage dtype, vectors fp32) and fp32 gradients per direction
     void* params = nullptr;
     float* grads[2] = {nullptr, nullptr};
-    // per (direction, chunk, layer): 1 while the layer's gradients are logically zero.  The buffer
-    // contents are then undefined and the next backward overwrites them instead of adding, which
-    // saves both the clearing pass and the first read of every read-modify-write.
+    // per (direction, chunk, layer): bit 0 set while the layer's weight-matrix gradients are
+    // logically zero, bit 1 the same for its vector gradients (biases, LayerNorm).  The buffer
+    // contents are then undefined and the next contribution overwrites them instead of adding,
+    // which saves both the clearing pass and the first read of every read-modify-write.
     std::vector<uint8_t> grad_clean[2];
+    // Grouped weight gradients: per (direction, chunk) the micro-batches waiting for their group.
+    int wgrad_group = 1;
+    std::vector<PendGroup> pend[2];
+    std::vector<void*> pend_pool;                    // idle PendingMb buffers
+    size_t q_dz = 0, q_du = 0, q_dy = 0, q_dqkv = 0, q_layer_bytes = 0;
+    int slot_capacity = 8;                           // most live stashes (held ones come on top)
     // Each weight matrix is also kept transposed ([out,in]) so that the forward GEMMs read both
     // operands contraction-major like the data-gradient GEMMs do; slots BP_N_TENSORS.. hold them.
     size_t p_off[BP_N_TENSORS + 4], g_off[BP_N_TENSORS], p_layer_bytes = 0, g_layer_bytes = 0;
@@ -118,6 +132,12 @@ struct Stage {
     int acquire_slot(int chunk, int mb, int* out);
     int live_slots() const;
 
+    int wgrad_one(int dir, int chunk, int l, int k, const void* cur_x, const void* cur_dy, int acc,
+                  hipStream_t ss);
+    int release_group(PendGroup& grp, hipStream_t ss);
+    int flush_group(int dir, int chunk);
+    int flush_all();
+    int drop_pending();
     int gemm(const void* A, int lda, int a_t, const void* Bm, int ldb, int b_t, void* C, int ldc,
              int M, int N, int K, const float* bias, const void* residual, int accumulate,
              hipStream_t on = nullptr, bool use_on = false);

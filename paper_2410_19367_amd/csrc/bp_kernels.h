@@ -11,6 +11,8 @@ enum DType { F32 = 0, BF16 = 1 };
 
 inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
 
+constexpr int kMaxGemmSegments = 4;
+
 // C = op(A) op(B) (+bias) (+residual)  or  C(fp32) += op(A) op(B).
 //   op(A)[m,k] = a_t ? A[k*lda + m] : A[m*lda + k]
 //   op(B)[k,n] = b_t ? B[n*ldb + k] : B[k*ldb + n]
@@ -28,6 +30,13 @@ struct GemmArgs {
     // order and applies the epilogue.  Null: never split.
     float* split_ws = nullptr;
     size_t split_ws_elems = 0;
+    // Optional further contraction segments: the product runs over nseg operand pairs
+    // (A, B), (A_more[0], B_more[0]), ... of K each, all with the same lda / ldb, as if the pairs
+    // were concatenated along the contraction index (weight gradient of several micro-batches in
+    // one pass over the fp32 accumulator).
+    int nseg = 1;
+    const void* A_more[kMaxGemmSegments - 1] = {};
+    const void* B_more[kMaxGemmSegments - 1] = {};
 };
 
 // picks the MFMA kernel when the shape allows it, else the generic one
@@ -35,6 +44,8 @@ hipError_t launch_gemm(int dtype, const GemmArgs& g, hipStream_t stream);
 hipError_t launch_gemm_generic(int dtype, const GemmArgs& g, hipStream_t stream);
 bool gemm_mfma_supported(const GemmArgs& g);                       // bf16 only
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t stream);
+hipError_t launch_gemm_per_segment(const GemmArgs& g, hipStream_t stream,
+                                   hipError_t (*one)(const GemmArgs&, hipStream_t));
 
 // rows kept per partial of a column reduction
 constexpr int kColsumRows = 32;

@@ -35,6 +35,24 @@ int bp_op_gemm(int dtype, int a_t, int b_t, int M, int N, int K, const void* A, 
     BP_OP_LAUNCH(bp::launch_gemm(dtype, g, (hipStream_t)stream));
 }
 
+int bp_op_wgrad_group(int dtype, int M, int N, int T, int n, const void* const* X, const void* const* dY,
+                      float* dW, int overwrite, void* stream) {
+    if (check_dtype(dtype)) return BP_EINVAL;
+    if (!X || !dY || !dW) return fail(BP_EINVAL, "null pointer");
+    if (M <= 0 || N <= 0 || T <= 0) return fail(BP_EINVAL, "M, N, T must be positive");
+    if (n < 1 || n > bp::kMaxGemmSegments)
+        return fail(BP_EINVAL, "n = %d outside 1..%d", n, bp::kMaxGemmSegments);
+    for (int i = 0; i < n; ++i)
+        if (!X[i] || !dY[i]) return fail(BP_EINVAL, "null operand %d", i);
+    bp::GemmArgs g;
+    g.A = X[0]; g.B = dY[0]; g.C = dW; g.bias = nullptr; g.residual = nullptr;
+    g.M = M; g.N = N; g.K = T; g.lda = M; g.ldb = N; g.ldc = N;
+    g.a_t = 1; g.b_t = 0; g.accumulate = overwrite ? 2 : 1;
+    g.nseg = n;
+    for (int i = 1; i < n; ++i) { g.A_more[i - 1] = X[i]; g.B_more[i - 1] = dY[i]; }
+    BP_OP_LAUNCH(bp::launch_gemm(dtype, g, (hipStream_t)stream));
+}
+
 int bp_op_layernorm_fwd(int dtype, int T, int H, const void* x, const float* gamma, const float* beta,
                         float eps, void* out, float* mean, float* rstd, void* stream) {
     if (check_dtype(dtype)) return BP_EINVAL;

@@ -246,7 +246,7 @@ int Stage::run_schedule(const bp_op* order, int n_ops, int D, const void* inputs
         sched_n = N;
     }
     // an order may keep every (stage, mb) stashed at once; slots get memory only when used
-    if ((int)slots.size() < 2 * D * N) slots.resize((size_t)2 * D * N);
+    if (slot_capacity < 2 * D * N) slot_capacity = 2 * D * N;
 
     if ((rc = zero_grad())) return rc;
     const int last = 2 * D - 1;

@@ -125,6 +125,8 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     if (opt.dtype != BP_F32 && opt.dtype != BP_BF16) return fail(BP_EINVAL, "unknown dtype %d", opt.dtype);
     if (opt.n_chunks < 0 || opt.mlp < 0 || opt.max_inflight < 0 || opt.ln_eps < 0)
         return fail(BP_EINVAL, "negative option");
+    if (opt.wgrad_group < 0 || opt.wgrad_group > kMaxGemmSegments)
+        return fail(BP_EINVAL, "wgrad_group %d outside 0..%d", opt.wgrad_group, kMaxGemmSegments);
     if (opt.mlp % 8) return fail(BP_ESHAPE, "mlp width must be a multiple of 8");
     if ((size_t)seq * sizeof(float) * 2 > 56000)
         return fail(BP_ESHAPE, "seq %d too long for the attention kernels", seq);
@@ -141,6 +143,9 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     st->eps = opt.ln_eps > 0 ? opt.ln_eps : 1e-5f;
     st->stream = (hipStream_t)opt.hip_stream;
     st->esz = dtype_size(st->dtype);
+    st->wgrad_group = opt.wgrad_group ? opt.wgrad_group : std::min(4, std::max(1, 8192 / st->T));
+    st->pend[0].resize(st->n_chunks);
+    st->pend[1].resize(st->n_chunks);
 
     // parameter and gradient layout: one blob each, tensors 256-byte aligned
     size_t poff = 0, goff = 0;
@@ -175,6 +180,10 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     st->s_lse = take((size_t)st->B * st->heads * st->S * sizeof(float));
     st->s_layer_bytes = so;
     st->slots.resize(st->max_inflight);
+    st->slot_capacity = st->max_inflight;
+    so = 0;
+    st->q_dz = take(TH); st->q_du = take(TF); st->q_dy = take(TH); st->q_dqkv = take(3 * TH);
+    st->q_layer_bytes = so;
 
     // backward workspaces
     const size_t big = std::max((size_t)st->F, (size_t)3 * st->H);
@@ -213,8 +222,8 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     hipError_t e = hipMemsetAsync(st->params, 0, n_layers * poff, st->stream);
     if (e == hipSuccess) e = launch_fill_f32(st->grads[0], n_layers * goff / 4, 0.f, st->stream);
     if (e == hipSuccess) e = launch_fill_f32(st->grads[1], n_layers * goff / 4, 0.f, st->stream);
-    st->grad_clean[0].assign(n_layers, 1);
-    st->grad_clean[1].assign(n_layers, 1);
+    st->grad_clean[0].assign(n_layers, 3);
+    st->grad_clean[1].assign(n_layers, 3);
     for (int c = 0; c < st->n_chunks && e == hipSuccess; ++c)
         for (int l = 0; l < st->L && e == hipSuccess; ++l) {
             e = launch_fill_f32((float*)st->param(c, l, BP_LN1_G), st->H, 1.f, st->stream);
@@ -246,6 +255,10 @@ Stage::~Stage() {
     hipFree(grads[0]);
     hipFree(grads[1]);
     for (auto& s : slots) { hipFree(s.buf); if (s.side_done) hipEventDestroy(s.side_done); }
+    for (int dir = 0; dir < 2; ++dir)
+        for (auto& grp : pend[dir])
+            for (auto& it : grp.items) hipFree(it.buf);
+    for (auto b : pend_pool) hipFree(b);
     for (int p = 0; p < 2; ++p) {
         hipFree(ws_big1[p]); hipFree(ws_big2[p]); hipFree(ws_h1[p]); hipFree(ws_h2[p]); hipFree(ws_h5[p]);
         hipFree(ws_colsum[p]);
@@ -313,8 +326,9 @@ int Stage::get_grad(int chunk, int layer, int id, float* host, size_t n) {
     int rc = check_tensor(chunk, layer, id, n);
     if (rc) return rc;
     if (!host) return fail(BP_EINVAL, "host pointer is null");
+    if ((rc = flush_all())) return rc;
     if ((rc = sync_all())) return rc;
-    if (grad_clean[0][(size_t)chunk * L + layer]) {     // nothing accumulated since the last clear
+    if (grad_clean[0][(size_t)chunk * L + layer] & (tensor_is_matrix(id) ? 1 : 2)) {   // nothing since the last clear
         memset(host, 0, n * sizeof(float));
         return BP_OK;
     }
@@ -327,28 +341,134 @@ int Stage::get_grad(int chunk, int layer, int id, float* host, size_t n) {
 
 int Stage::zero_grad() {
     // host bookkeeping only: kernels enqueued before this call still add into the old contents,
-    // kernels enqueued after it see the layer as clear and overwrite
-    grad_clean[0].assign(grad_clean[0].size(), 1);
-    grad_clean[1].assign(grad_clean[1].size(), 1);
+    // kernels enqueued after it see the layer as clear and overwrite.  Weight gradients still
+    // waiting for their group belong to what is being cleared and are dropped.
+    int rc = drop_pending();
+    if (rc) return rc;
+    grad_clean[0].assign(grad_clean[0].size(), 3);
+    grad_clean[1].assign(grad_clean[1].size(), 3);
     return BP_OK;
 }
 
 int Stage::merge_directions() {
+    int rc = flush_all();
+    if (rc) return rc;
     const size_t n = g_layer_bytes / sizeof(float);
     Scoped sc(this, BP_K_OTHER, 0, 0);
     // every writer of the gradient buffers runs on the side stream, so the merge goes there too
     hipStream_t gs = side_stream();
     for (size_t i = 0; i < grad_clean[0].size(); ++i) {
-        if (grad_clean[1][i]) continue;
+        const int c0 = grad_clean[0][i], c1 = grad_clean[1][i];
+        if (c1 == 3) continue;
+        if (c1 != 0 || (c0 != 0 && c0 != 3))
+            return fail(BP_ESTATE, "merge_directions: layer %zu is partly written", i);
         float* g0 = (float*)((char*)grads[0] + i * g_layer_bytes);
         float* g1 = (float*)((char*)grads[1] + i * g_layer_bytes);
-        hipError_t e = grad_clean[0][i]
-                           ? hipMemcpyAsync(g0, g1, g_layer_bytes, hipMemcpyDeviceToDevice, gs)
-                           : launch_add_f32(g0, g1, n, gs);
+        hipError_t e = c0 == 3 ? hipMemcpyAsync(g0, g1, g_layer_bytes, hipMemcpyDeviceToDevice, gs)
+                               : launch_add_f32(g0, g1, n, gs);
         if (e != hipSuccess) return fail(BP_EHIP, "merge_directions: %s", hipGetErrorString(e));
         grad_clean[0][i] = 0;
-        grad_clean[1][i] = 1;
+        grad_clean[1][i] = 3;
     }
+    return BP_OK;
+}
+
+// ------------------------------------------------------------------ grouped weight gradients
+
+// Gradient of weight matrix k (0: W2, 1: W1, 2: Wo, 3: Wqkv) of one layer over the group's waiting
+// micro-batches plus, when cur_x is given, the current one: a single GEMM whose contraction runs
+// over all their tokens.
+int Stage::wgrad_one(int dir, int chunk, int l, int k, const void* cur_x, const void* cur_dy, int acc,
+                     hipStream_t ss) {
+    static const int ids[4] = {BP_W2, BP_W1, BP_WO, BP_WQKV};
+    const size_t sx[4] = {s_g, s_m, s_ctx, s_a}, qy[4] = {q_dz, q_du, q_dy, q_dqkv};
+    const int Mk[4] = {F, H, H, H}, Nk[4] = {H, F, H, 3 * H};
+    const PendGroup& grp = pend[dir][chunk];
+    const void* xs[kMaxGemmSegments];
+    const void* ys[kMaxGemmSegments];
+    int n = 0;
+    for (const PendingMb& it : grp.items) {
+        if (n >= kMaxGemmSegments) return fail(BP_ESTATE, "weight-gradient group overflow");
+        xs[n] = (const char*)slots[it.slot].buf + (size_t)l * s_layer_bytes + sx[k];
+        ys[n] = (const char*)it.buf + (size_t)l * q_layer_bytes + qy[k];
+        ++n;
+    }
+    if (cur_x) {
+        if (n >= kMaxGemmSegments) return fail(BP_ESTATE, "weight-gradient group overflow");
+        xs[n] = cur_x; ys[n] = cur_dy; ++n;
+    }
+    if (n == 0) return BP_OK;
+    GemmArgs g;
+    g.A = xs[0]; g.B = ys[0]; g.C = grad(dir, chunk, l, ids[k]); g.bias = nullptr; g.residual = nullptr;
+    g.M = Mk[k]; g.N = Nk[k]; g.K = T; g.lda = Mk[k]; g.ldb = Nk[k]; g.ldc = Nk[k];
+    g.a_t = 1; g.b_t = 0; g.accumulate = acc;
+    g.nseg = n;
+    for (int i = 1; i < n; ++i) { g.A_more[i - 1] = xs[i]; g.B_more[i - 1] = ys[i]; }
+    Scoped sc(this, BP_K_GEMM, 2.0 * Mk[k] * Nk[k] * (double)T * n, 0);
+    hipError_t e = launch_gemm(dtype, g, ss);
+    if (e != hipSuccess) return fail(BP_EHIP, "weight-gradient GEMM: %s", hipGetErrorString(e));
+    return BP_OK;
+}
+
+// The group's stashes and buffers become reusable once the side stream has passed this point.
+int Stage::release_group(PendGroup& grp, hipStream_t ss) {
+    for (PendingMb& it : grp.items) {
+        StashSlot& sl = slots[it.slot];
+        if (ss != stream) {
+            hipError_t e = hipSuccess;
+            if (!sl.side_done) e = hipEventCreateWithFlags(&sl.side_done, hipEventDisableTiming);
+            if (e == hipSuccess) e = hipEventRecord(sl.side_done, ss);
+            if (e != hipSuccess) return fail(BP_EHIP, "release_group: %s", hipGetErrorString(e));
+            sl.side_pending = true;
+        }
+        sl.held = false;
+        pend_pool.push_back(it.buf);
+    }
+    grp.items.clear();
+    return BP_OK;
+}
+
+int Stage::flush_group(int dir, int chunk) {
+    PendGroup& grp = pend[dir][chunk];
+    if (grp.items.empty()) return BP_OK;
+    hipStream_t ss = side_stream();
+    if (ss != stream) {     // the waiting gradients were written on the main stream
+        hipError_t e = hipEventRecord(ev_ready[0], stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(ss, ev_ready[0], 0);
+        if (e != hipSuccess) return fail(BP_EHIP, "flush_group: %s", hipGetErrorString(e));
+    }
+    int rc;
+    for (int l = L - 1; l >= 0; --l) {
+        uint8_t& clean = grad_clean[dir][(size_t)chunk * L + l];
+        for (int k = 0; k < 4; ++k)
+            if ((rc = wgrad_one(dir, chunk, l, k, nullptr, nullptr, (clean & 1) ? 2 : 1, ss))) return rc;
+        clean &= ~1;
+    }
+    if ((rc = release_group(grp, ss))) return rc;
+    if (ss != stream) {     // the next backward must not overwrite buffers these GEMMs still read
+        hipError_t e = hipEventRecord(ev_misc, ss);
+        if (e != hipSuccess) return fail(BP_EHIP, "flush_group: %s", hipGetErrorString(e));
+        call_done_pending = true;
+    }
+    return BP_OK;
+}
+
+int Stage::flush_all() {
+    for (int dir = 0; dir < 2; ++dir)
+        for (int c = 0; c < n_chunks; ++c) {
+            int rc = flush_group(dir, c);
+            if (rc) return rc;
+        }
+    return BP_OK;
+}
+
+int Stage::drop_pending() {
+    hipStream_t ss = side_stream();
+    for (int dir = 0; dir < 2; ++dir)
+        for (auto& grp : pend[dir]) {
+            int rc = release_group(grp, ss);      // column sums of those calls may still be running
+            if (rc) return rc;
+        }
     return BP_OK;
 }
 
@@ -392,23 +512,31 @@ int Stage::find_slot(int chunk, int mb) const {
 int Stage::acquire_slot(int chunk, int mb, int* out) {
     if (find_slot(chunk, mb) >= 0)
         return fail(BP_ESTATE, "forward(chunk %d, mb %d) while its stash is still live", chunk, mb);
+    int live = 0, pick = -1;
     for (size_t i = 0; i < slots.size(); ++i) {
-        if (slots[i].live) continue;
-        if (!slots[i].buf) {
-            int rc = dev_alloc(&slots[i].buf, (size_t)L * s_layer_bytes);
-            if (rc) return rc;
-        }
-        if (slots[i].side_pending) {
-            // the previous owner's weight-gradient kernels may still be reading this stash
-            hipError_t e = hipStreamWaitEvent(stream, slots[i].side_done, 0);
-            if (e != hipSuccess) return fail(BP_EHIP, "stash reuse wait: %s", hipGetErrorString(e));
-            slots[i].side_pending = false;
-        }
-        slots[i].live = true; slots[i].chunk = chunk; slots[i].mb = mb;
-        *out = (int)i;
-        return BP_OK;
+        live += slots[i].live;
+        if (pick < 0 && !slots[i].live && !slots[i].held) pick = (int)i;
     }
-    return fail(BP_ESTATE, "all %d stash slots are live (max_inflight)", max_inflight);
+    if (live >= slot_capacity)
+        return fail(BP_ESTATE, "all %d stash slots are live (max_inflight)", slot_capacity);
+    if (pick < 0) {         // every idle slot is held by a weight-gradient group: add one
+        slots.emplace_back();
+        pick = (int)slots.size() - 1;
+    }
+    StashSlot& sl = slots[pick];
+    if (!sl.buf) {
+        int rc = dev_alloc(&sl.buf, (size_t)L * s_layer_bytes);
+        if (rc) return rc;
+    }
+    if (sl.side_pending) {
+        // the previous owner's weight-gradient kernels may still be reading this stash
+        hipError_t e = hipStreamWaitEvent(stream, sl.side_done, 0);
+        if (e != hipSuccess) return fail(BP_EHIP, "stash reuse wait: %s", hipGetErrorString(e));
+        sl.side_pending = false;
+    }
+    sl.live = true; sl.chunk = chunk; sl.mb = mb;
+    *out = pick;
+    return BP_OK;
 }
 
 // ------------------------------------------------------------------ forward of one chunk
@@ -523,16 +651,45 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         layer_done_pending[0] = layer_done_pending[1] = false;
     }
 
+    // Grouped weight gradients: unless this call completes its group, the four weight-gradient
+    // GEMMs of every layer are postponed; the tensors they need (dz, du, dy, dqkv) are then
+    // produced straight into a buffer that lives until the group is complete, and the stash stays
+    // held.  The call that completes the group multiplies over all waiting micro-batches at once.
+    PendGroup& grp = pend[dir][chunk];
+    const bool defer = (int)grp.items.size() + 1 < wgrad_group;
+    char* qbuf = nullptr;
+    if (defer) {
+        if (!pend_pool.empty()) {
+            qbuf = (char*)pend_pool.back();
+            pend_pool.pop_back();
+        } else if ((rc = dev_alloc((void**)&qbuf, (size_t)L * q_layer_bytes))) {
+            return rc;
+        }
+    }
+    struct PoolGuard {      // hand the buffer back if the call fails half-way
+        Stage* st; char*& b;
+        ~PoolGuard() { if (b) st->pend_pool.push_back(b); }
+    } guard{this, qbuf};
+
     const void* dz = grad_out;
+    if (defer) {            // the caller may reuse grad_out right after this call
+        void* keep = qbuf + (size_t)(L - 1) * q_layer_bytes + q_dz;
+        BP_HIP(hipMemcpyAsync(keep, grad_out, (size_t)T * H * esz, hipMemcpyDeviceToDevice, stream));
+        dz = keep;
+    }
     for (int l = L - 1; l >= 0; --l) {
         const int p = l & 1;
         char* sb = (char*)slots[slot].buf + (size_t)l * s_layer_bytes;
         auto P = [&](int id) { return param(chunk, l, id); };
         auto G = [&](int id) { return grad(dir, chunk, l, id); };
         uint8_t& clean = grad_clean[dir][(size_t)chunk * L + l];
-        const int acc = clean ? 2 : 1;          // first contribution after a clear overwrites
-        void* dx = l == 0 ? grad_in : ws_dx[l % 3];
-        void *big1 = ws_big1[p], *big2 = ws_big2[p], *h1 = ws_h1[p], *h2 = ws_h2[p], *h5 = ws_h5[p];
+        const int acc = (clean & 1) ? 2 : 1;    // first contribution after a clear overwrites
+        char* qb = defer ? qbuf + (size_t)l * q_layer_bytes : nullptr;
+        void* dx = l == 0 ? grad_in : defer ? (void*)(qb - q_layer_bytes + q_dz) : ws_dx[l % 3];
+        void* big1 = defer ? (void*)(qb + q_du) : ws_big1[p];
+        void* big2 = defer ? (void*)(qb + q_dqkv) : ws_big2[p];
+        void* h2 = defer ? (void*)(qb + q_dy) : ws_h2[p];
+        void *h1 = ws_h1[p], *h5 = ws_h5[p];
         if (two && layer_done_pending[p]) {     // workspaces of this parity still read by the side stream?
             BP_HIP(hipStreamWaitEvent(stream, ev_layer_done[p], 0));
             layer_done_pending[p] = false;
@@ -548,7 +705,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
 
         // z = y + g W2 + b2
         BP_HIP(hand_over(0));                                                                               // dz
-        if ((rc = gemm(sb + s_g, F, 1, dz, H, 0, G(BP_W2), H, F, H, T, nullptr, nullptr, acc, ss, true))) return rc;   // dW2
+        if (!defer && (rc = wgrad_one(dir, chunk, l, 0, sb + s_g, dz, acc, ss))) return rc;                 // dW2
         if ((rc = gemm(dz, H, 0, P(BP_W2), H, 1, big1, F, T, F, H, nullptr, nullptr, 0))) return rc;        // dg
         {   // du = dg * gelu'(u + b1); db1 partials (folded with the other column sums below)
             Scoped sc(this, BP_K_GELU_BWD, 0, 3.0 * T * F * esz);
@@ -556,7 +713,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
                                       stream));
         }
         BP_HIP(hand_over(1));                                                                               // du
-        if ((rc = gemm(sb + s_m, H, 1, big1, F, 0, G(BP_W1), F, H, F, T, nullptr, nullptr, acc, ss, true))) return rc;  // dW1
+        if (!defer && (rc = wgrad_one(dir, chunk, l, 1, sb + s_m, big1, acc, ss))) return rc;              // dW1
         if ((rc = gemm(big1, F, 0, P(BP_W1), F, 1, h1, H, T, H, F, nullptr, nullptr, 0))) return rc;        // dm
         {   // dy = dz + LN2bwd(dm)
             Scoped sc(this, BP_K_LN_BWD, 0, 4 * unit);
@@ -565,7 +722,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         }
         // y = x + ctx Wo + bo
         BP_HIP(hand_over(2));                                                                               // dy
-        if ((rc = gemm(sb + s_ctx, H, 1, h2, H, 0, G(BP_WO), H, H, H, T, nullptr, nullptr, acc, ss, true))) return rc;  // dWo
+        if (!defer && (rc = wgrad_one(dir, chunk, l, 2, sb + s_ctx, h2, acc, ss))) return rc;              // dWo
         if ((rc = gemm(h2, H, 0, P(BP_WO), H, 1, ws_h4, H, T, H, H, nullptr, nullptr, 0))) return rc;       // dctx
         {
             AttnArgs a{B, S, heads, d, causal ? 1 : 0, ln, sb + s_qkv, sb + s_ctx, (float*)(sb + s_lse),
@@ -575,14 +732,13 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         }
         // qkv = a Wqkv + bqkv
         BP_HIP(hand_over(3));                                                                               // dqkv
-        if ((rc = gemm(sb + s_a, H, 1, big2, 3 * H, 0, G(BP_WQKV), 3 * H, H, 3 * H, T, nullptr, nullptr, acc, ss, true)))
-            return rc;
+        if (!defer && (rc = wgrad_one(dir, chunk, l, 3, sb + s_a, big2, acc, ss))) return rc;              // dWqkv
         if ((rc = gemm(big2, 3 * H, 0, P(BP_WQKV), 3 * H, 1, h5, H, T, H, 3 * H, nullptr, nullptr, 0))) return rc;  // da
         BP_HIP(hand_over(4));                                                                               // da
         {   // every bias and LayerNorm-parameter gradient of the layer in one batched reduction
             ColsumBatch cb;
             cb.n = 6;
-            cb.overwrite = clean ? 1 : 0;
+            cb.overwrite = (clean & 2) ? 1 : 0;
             cb.jobs[0] = ColsumJob{dz, nullptr, nullptr, nullptr, H, G(BP_B2), nullptr, p_b2};
             cb.jobs[1] = ColsumJob{h1, sb + s_y, (const float*)(sb + s_mean2), (const float*)(sb + s_rstd2), H,
                                    G(BP_LN2_B), G(BP_LN2_G), p_ln2};
@@ -594,7 +750,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
             Scoped sc(this, BP_K_COLSUM, 0, 0);
             BP_LAUNCH(launch_colsum_batch(dtype, T, cb, ss));
         }
-        clean = 0;
+        clean &= defer ? ~2 : 0;
         if (two) {
             BP_HIP(hipEventRecord(ev_layer_done[p], ss));
             layer_done_pending[p] = true;
@@ -619,17 +775,26 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         }
         dz = dx;
     }
+    slots[slot].live = false;
+    if (defer) {
+        slots[slot].held = true;
+        grp.items.push_back(PendingMb{slot, qbuf});
+        qbuf = nullptr;                         // owned by the group now
+    } else {
+        if ((rc = release_group(grp, ss))) return rc;
+        if (two) {
+            // the stash may be handed to a new forward only after the side stream has read it
+            if (!slots[slot].side_done)
+                BP_HIP(hipEventCreateWithFlags(&slots[slot].side_done, hipEventDisableTiming));
+            BP_HIP(hipEventRecord(slots[slot].side_done, ss));
+            slots[slot].side_pending = true;
+        }
+    }
     if (two) {
-        // the stash may be handed to a new forward only after the side stream has read it
-        if (!slots[slot].side_done)
-            BP_HIP(hipEventCreateWithFlags(&slots[slot].side_done, hipEventDisableTiming));
-        BP_HIP(hipEventRecord(slots[slot].side_done, ss));
-        slots[slot].side_pending = true;
         BP_HIP(hipEventRecord(ev_misc, ss));
         call_done_pending = true;
     }
 #undef BP_HIP
-    slots[slot].live = false;
     return BP_OK;
 }
 

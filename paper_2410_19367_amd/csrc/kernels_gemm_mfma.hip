@@ -29,10 +29,17 @@ constexpr int BK = 64;
 __device__ __forceinline__ int kmajor_off(int row, int chunk) {
     return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4);
 }
-// r-major tile [64][R]: 2R bytes per k-row, 16-byte chunk c stored at c ^ ((k&3)<<2)
+// r-major tile [64][R]: 2R bytes per k-row, 16-byte chunk c stored at c ^ rmajor_swz(k).  A transpose
+// read touches 64 contiguous bytes in each of four consecutive k-rows; the XOR puts those four
+// pieces into different 64-byte bank groups.  With R a multiple of 128 the rows start 0 mod 256
+// bytes apart (shift by 0/64/128/192 bytes); with R = 192 they alternate 0/128, so rows 2 and 3
+// only need a 64-byte shift, which also keeps the XOR inside the row's 24 chunks.
+template <int R> __device__ __forceinline__ int rmajor_swz(int k) {
+    return R % 128 == 0 ? ((k & 3) << 2) : (((k >> 1) & 1) << 2);
+}
 template <int R>
 __device__ __forceinline__ int rmajor_off(int k, int chunk) {
-    return k * (2 * R) + ((chunk ^ ((k & 3) << 2)) << 4);
+    return k * (2 * R) + ((chunk ^ rmajor_swz<R>(k)) << 4);
 }
 
 template <int R> constexpr int tile_bytes() { return R * BK * 2; }
@@ -250,7 +257,7 @@ struct DmaPlan {
             const int P = (wave + NW * i) * 64 + lane;          // 16-byte position in the tile
             if (RMAJOR) {
                 const int krow = P / (R / 8), p = P % (R / 8);
-                goff[i] = krow * ld + ((p ^ ((krow & 3) << 2)) << 3);
+                goff[i] = krow * ld + ((p ^ rmajor_swz<R>(krow)) << 3);
             } else {
                 const int row = P / (BKT / 8), p = P % (BKT / 8);
                 goff[i] = row * ld + ((p ^ kmaj_swz<BKT>(row)) << 3);
@@ -284,6 +291,12 @@ __device__ __forceinline__ bf16x8 read_frag2(const char* lds, int row0, int kk, 
     }
 }
 
+constexpr int rows_per_instr(int lanes_per_row) {
+    int r = 1;
+    while (2 * r * lanes_per_row <= 64 && 2 * r <= 32) r *= 2;
+    return r;
+}
+
 template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n, int splits) {
     constexpr int NW = WM * WN;
@@ -308,14 +321,34 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction
     const int wm = wave / WN, wn = wave % WN;
 
-    const int k_len = g.K / splits;
-    const size_t k_begin = (size_t)sp * k_len;
-    const bf16_t* a_base = A_RMAJOR ? (const bf16_t*)g.A + m0 + k_begin * g.lda
-                                    : (const bf16_t*)g.A + (size_t)m0 * g.lda + k_begin;
-    const bf16_t* b_base = B_RMAJOR ? (const bf16_t*)g.B + n0 + k_begin * g.ldb
-                                    : (const bf16_t*)g.B + (size_t)n0 * g.ldb + k_begin;
+    // The contraction runs over g.nseg operand pairs of g.K each; this block owns slices
+    // [sp * nk, (sp + 1) * nk) of the concatenation.  (seg, kl) is the position of the next slice
+    // to request and (a_next, b_next) its tile origin.
+    const int nk_seg = g.K / BKT;
+    const int nk = nk_seg * g.nseg / splits;
     const size_t a_step = A_RMAJOR ? (size_t)BKT * g.lda : BKT;
     const size_t b_step = B_RMAJOR ? (size_t)BKT * g.ldb : BKT;
+    auto a_origin = [&](int sgm) {
+        const bf16_t* A = (const bf16_t*)(sgm == 0 ? g.A : sgm == 1 ? g.A_more[0] : sgm == 2 ? g.A_more[1] : g.A_more[2]);
+        return A_RMAJOR ? A + m0 : A + (size_t)m0 * g.lda;
+    };
+    auto b_origin = [&](int sgm) {
+        const bf16_t* Bp = (const bf16_t*)(sgm == 0 ? g.B : sgm == 1 ? g.B_more[0] : sgm == 2 ? g.B_more[1] : g.B_more[2]);
+        return B_RMAJOR ? Bp + n0 : Bp + (size_t)n0 * g.ldb;
+    };
+    int seg = (sp * nk) / nk_seg, kl = (sp * nk) % nk_seg;
+    const bf16_t* a_next = a_origin(seg) + kl * a_step;
+    const bf16_t* b_next = b_origin(seg) + kl * b_step;
+    auto advance = [&]() {
+        a_next += a_step;
+        b_next += b_step;
+        if (++kl == nk_seg && seg + 1 < g.nseg) {
+            kl = 0;
+            ++seg;
+            a_next = a_origin(seg);
+            b_next = b_origin(seg);
+        }
+    };
 
     DmaPlan<BM, BKT, NW, A_RMAJOR> pa;
     DmaPlan<BN, BKT, NW, B_RMAJOR> pb;
@@ -331,12 +364,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nk = k_len / BKT;
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) {
         if (s < nk) {
-            pa.issue(a_base + s * a_step, smem + s * STAGE, wave);
-            pb.issue(b_base + s * b_step, smem + s * STAGE + A_BYTES, wave);
+            pa.issue(a_next, smem + s * STAGE, wave);
+            pb.issue(b_next, smem + s * STAGE + A_BYTES, wave);
+            advance();
         }
     }
 
@@ -348,8 +381,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
         __syncthreads();
         if (kt + NS - 1 < nk) {
             char* st = smem + ((kt + NS - 1) % NS) * STAGE;
-            pa.issue(a_base + (size_t)(kt + NS - 1) * a_step, st, wave);
-            pb.issue(b_base + (size_t)(kt + NS - 1) * b_step, st + A_BYTES, wave);
+            pa.issue(a_next, st, wave);
+            pb.issue(b_next, st + A_BYTES, wave);
+            advance();
         }
         const char* sa = smem + (kt % NS) * STAGE;
         const char* sb = sa + A_BYTES;
@@ -407,29 +441,33 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
             for (int v = 0; v < 16; ++v)
                 ep[(8 * (v >> 2) + 4 * h + (v & 3)) * PITCH + j * 32 + (lane & 31)] = acc[i][j][v];
         const int m_base = m0 + wm * (BM / WM) + i * 32;
+        // rows per instruction: the largest power of two whose lanes fit in a wave (a 96-wide wave
+        // tile leaves a quarter of the lanes idle here)
         if (splits > 1) {           // fp32 partial of this K slice, row-major [M][N]
-            constexpr int LPR = WTN / 4, RPI = 64 / LPR;
+            constexpr int LPR = WTN / 4, RPI = rows_per_instr(LPR);
             const int col = (lane % LPR) * 4;
             float* slab = g.split_ws + (size_t)sp * g.M * g.N;
 #pragma unroll
             for (int r = 0; r < 32; r += RPI) {
                 const int row = r + lane / LPR;
+                if (LPR * RPI < 64 && lane >= LPR * RPI) continue;
                 *reinterpret_cast<f32x4*>(slab + (size_t)(m_base + row) * g.N + n_base + col) =
                     *reinterpret_cast<const f32x4*>(ep + row * PITCH + col);
             }
         } else if (g.accumulate) {
-            constexpr int LPR = WTN / 4, RPI = 64 / LPR;        // lanes per row, rows per instruction
+            constexpr int LPR = WTN / 4, RPI = rows_per_instr(LPR);   // lanes per row, rows per instruction
             const int col = (lane % LPR) * 4;
 #pragma unroll
             for (int r = 0; r < 32; r += RPI) {
                 const int row = r + lane / LPR;
+                if (LPR * RPI < 64 && lane >= LPR * RPI) continue;
                 const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * PITCH + col);
                 f32x4* c = reinterpret_cast<f32x4*>((float*)g.C + (size_t)(m_base + row) * g.ldc + n_base + col);
                 if (g.accumulate == 2) *c = v;      // first contribution after a clear: no read
                 else *c = *c + v;
             }
         } else {
-            constexpr int LPR = WTN / 8, RPI = 64 / LPR;
+            constexpr int LPR = WTN / 8, RPI = rows_per_instr(LPR);
             const int col = (lane % LPR) * 8;
             float bias[8];
 #pragma unroll
@@ -437,6 +475,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
 #pragma unroll
             for (int r = 0; r < 32; r += RPI) {
                 const int row = r + lane / LPR;
+                if (LPR * RPI < 64 && lane >= LPR * RPI) continue;
                 const f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * PITCH + col);
                 const f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * PITCH + col + 4);
                 float o[8] = {v0[0] + bias[0], v0[1] + bias[1], v0[2] + bias[2], v0[3] + bias[3],
@@ -555,6 +594,8 @@ bool gemm_mfma_supported(const GemmArgs& g) {
     auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
     if (g.K % 8 || g.lda % 8 || g.ldb % 8) return false;
     if (!al16(g.A) || !al16(g.B)) return false;
+    for (int i = 0; i + 1 < g.nseg; ++i)
+        if (!al16(g.A_more[i]) || !al16(g.B_more[i])) return false;
     // r-major operands are read in 8-element chunks along their row index
     if (g.a_t && g.M % 8) return false;
     if (!g.b_t && g.N % 8) return false;
@@ -563,12 +604,23 @@ bool gemm_mfma_supported(const GemmArgs& g) {
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
-    const bool aligned128 = g.M % 128 == 0 && g.N % 128 == 0 && g.K % BK == 0 && g.ldc % 8 == 0 &&
-                            al16(g.C) && (!g.residual || al16(g.residual));
-    if (!aligned128) return launch_cfg<128, 128, 2, 2, true>(g, s);
+    bool aligned128 = g.M % 128 == 0 && g.N % 128 == 0 && g.K % BK == 0 && g.ldc % 8 == 0 &&
+                      al16(g.C) && (!g.residual || al16(g.residual));
+    for (int i = 0; i + 1 < g.nseg; ++i) aligned128 = aligned128 && al16(g.A_more[i]) && al16(g.B_more[i]);
+    if (!aligned128) {
+        if (g.nseg == 1) return launch_cfg<128, 128, 2, 2, true>(g, s);
+        return launch_gemm_per_segment(g, s, [](const GemmArgs& h, hipStream_t st) {
+            return launch_cfg<128, 128, 2, 2, true>(h, st);
+        });
+    }
     // 256 x 256 tiles (8 waves) once they fill at least three quarters of the 256 CUs
     const bool aligned256 = g.M % 256 == 0 && g.N % 256 == 0;
     const long t256 = aligned256 ? (long)(g.M / 256) * (g.N / 256) : 0;
+    // 256 x 192 tiles when they fill the CUs better: e.g. N = 6144 gives 24 columns of 256 (192 tiles
+    // for M = 2048, a quarter of the CUs idle) but 32 columns of 192 (256 tiles)
+    auto fill = [](long t) { return t <= 0 ? 0.0 : (double)t / (double)(((t + 255) / 256) * 256); };
+    const long t192 = (g.M % 256 == 0 && g.N % 192 == 0) ? (long)(g.M / 256) * (g.N / 192) : 0;
+    if (t192 >= 192 && 0.95 * fill(t192) > fill(t256)) return launch_dma<256, 192, 4, 2, 2>(g, s);
     if (t256 >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s);
     // Few output tiles but a long K: 256x256 tiles on K slices keep the operand traffic per flop
     // at the large-tile level (128x128 tiles are bound by the per-CU load path) and still give
@@ -576,7 +628,8 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     if (t256 > 0 && g.split_ws) {
         int splits = (int)(256 / t256);
         if (splits > 4) splits = 4;
-        while (splits > 1 && (g.K % (splits * BK) || g.K / splits < 1024 ||
+        const long k_total = (long)g.K * g.nseg;
+        while (splits > 1 && (k_total % (splits * BK) || k_total / splits < 1024 ||
                               (size_t)splits * g.M * g.N > g.split_ws_elems))
             --splits;
         if (splits > 1 && t256 * splits >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s, splits);

@@ -46,14 +46,15 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 class GpuStage:
     """Drives one library stage object for a StageConfig."""
 
-    def __init__(self, cfg: si.StageConfig, max_inflight=0):
+    def __init__(self, cfg: si.StageConfig, max_inflight=0, wgrad_group=0):
         import paper_2410_19367_amd as bp
         self.bp = bp
         self.cfg = cfg
         self.h = bp.bp_stage_init_ex(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch,
                                      cfg.causal, n_chunks=cfg.n_chunks, mlp=cfg.mlp,
                                      dtype=bp.BP_BF16 if cfg.dtype == "bf16" else bp.BP_F32,
-                                     max_inflight=max_inflight, ln_eps=cfg.ln_eps)
+                                     max_inflight=max_inflight, ln_eps=cfg.ln_eps,
+                                     wgrad_group=wgrad_group)
 
     def close(self):
         if self.h is not None:
@@ -98,14 +99,14 @@ def make_oracle(cfg: si.StageConfig, params):
     return st
 
 
-def run_fwd_bwd_parity(cfg: si.StageConfig, n_micro=None, seed=0, ln_jitter=0.0, check=True):
+def run_fwd_bwd_parity(cfg: si.StageConfig, n_micro=None, seed=0, ln_jitter=0.0, check=True, wgrad_group=0):
     """F then B for each micro-batch on both sides; returns dict name -> rel err."""
     torch = torch_mod()
     n_micro = cfg.n_micro if n_micro is None else n_micro
     params = si.make_params(cfg, seed, ln_jitter)
     orc = make_oracle(cfg, params)
     errs = {}
-    with GpuStage(cfg) as g:
+    with GpuStage(cfg, wgrad_group=wgrad_group) as g:
         g.load_params(params)
         g.bp.bp_stage_zero_grad(g.h)
         for mb in range(n_micro):

@@ -233,3 +233,35 @@ def test_attention_wide_score_range(B, S, heads, d, causal):
     for name, sl in (("dq", slice(0, H)), ("dk", slice(H, 2 * H)), ("dv", slice(2 * H, 3 * H))):
         err = hz.rel_err(got[..., sl], dqkv_ref[..., sl])
         assert err <= 2e-2, (name, err)
+
+
+@pytest.mark.parametrize("M,N,T,n", [
+    (512, 768, 256, 2),        # 128-tile direct-to-LDS kernel, segment change between slices
+    (2048, 6144, 192, 3),      # 256x192 tiles
+    (4096, 4096, 128, 4),      # 256x256 tiles, four segments of two slices
+    (256, 256, 64, 4),         # one slice per segment
+    (200, 264, 136, 3),        # ragged: one launch per segment
+    (512, 768, 256, 1),
+])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("overwrite", [0, 1])
+def test_wgrad_group(M, N, T, n, dtype, overwrite):
+    """dW (+)= sum_i X_i^T dY_i over a group of micro-batches in one call."""
+    import torch
+    import paper_2410_19367_amd as bp
+    if dtype == "f32" and M * N > 2 ** 21:
+        pytest.skip("fp32 generic kernel: small shapes only")
+    dt = bp.BP_BF16 if dtype == "bf16" else bp.BP_F32
+    xs = [_randn(f"gx{i}", (T, M), dtype=dtype) for i in range(n)]
+    ys = [_randn(f"gy{i}", (T, N), dtype=dtype) for i in range(n)]
+    w0 = _randn("gw0", (M, N), dtype="f32")
+    ref = sum(x.astype(np.float64).T @ y.astype(np.float64) for x, y in zip(xs, ys))
+    if not overwrite:
+        ref = ref + w0
+    xd = [hz.to_dev(x, dtype) for x in xs]
+    yd = [hz.to_dev(y, dtype) for y in ys]
+    wd = _f32_dev(w0)
+    bp.bp_op_wgrad_group(dt, M, N, T, xd, yd, wd, overwrite)
+    torch.cuda.synchronize()
+    err = hz.rel_err(wd.cpu().numpy().astype(np.float64), ref)
+    assert err <= (2e-3 if dtype == "bf16" else 1e-5), err

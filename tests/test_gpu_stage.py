@@ -99,3 +99,47 @@ def test_zero_grad_semantics_across_iterations():
                 err = hz.rel_err(g.grad(0, l, name), orc.get_grad(0, l, name))
                 assert err <= hz.TOL[cfg.dtype], (l, name, err)
                 assert not g.grad(1, l, name).any(), ("chunk 1 never ran", l, name)
+
+
+@pytest.mark.parametrize("group", [1, 2, 3, 4])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_grouped_weight_gradients(group, dtype):
+    """Weight gradients computed over groups of 1..4 backward calls: five micro-batches give
+    complete groups plus a remainder that only the gradient read-out flushes; activations,
+    input gradients and all accumulated gradients must match the oracle either way."""
+    base = si.CONFIGS[1] if dtype == "bf16" else si.CONFIGS[0]
+    cfg = si.scaled(base, name=f"small_group{group}", layers=2, hidden=256, heads=2, seq=128,
+                    microbatch=2, n_micro=5, dtype=dtype, causal=True)
+    hz.run_fwd_bwd_parity(cfg, ln_jitter=0.1, wgrad_group=group)
+
+
+def test_grouped_weight_gradients_interleaved_chunks_and_directions():
+    """Groups are kept per (chunk, direction): backward calls of two chunks and both directions
+    interleave, with more stashes alive than any one group holds, and a clear in the middle of
+    a group discards that group's waiting contributions."""
+    cfg = si.scaled(si.CONFIGS[1], name="small_group_mix", layers=1, hidden=256, heads=2, seq=128,
+                    microbatch=1, n_micro=5, n_chunks=2)
+    params = si.make_params(cfg, 5, 0.1)
+    orc = hz.make_oracle(cfg, params)
+    with hz.GpuStage(cfg, max_inflight=12, wgrad_group=3) as g:
+        g.load_params(params)
+        xs = {mb: si.make_activation(cfg, "act_in", mb, 5) for mb in range(cfg.n_micro)}
+        gos = {mb: si.make_activation(cfg, "grad_out", mb, 5) for mb in range(cfg.n_micro)}
+        # a waiting contribution that the clear must discard
+        g.forward(0, 0, hz.to_dev(xs[0], cfg.dtype))
+        g.backward(0, 0, hz.to_dev(gos[0], cfg.dtype), direction=0)
+        g.bp.bp_stage_zero_grad(g.h)
+        for c in range(2):
+            for mb in range(cfg.n_micro):
+                g.forward(c, mb, hz.to_dev(xs[mb], cfg.dtype))
+                orc.forward(c, mb, xs[mb])
+        for mb in range(cfg.n_micro):
+            for c in (1, 0):
+                d = (mb + c) % 2
+                g.backward(c, mb, hz.to_dev(gos[mb], cfg.dtype), direction=d)
+                orc.backward(c, mb, gos[mb], d)
+        # get_grad reads the direction-0 accumulators
+        for c in range(2):
+            for name in si.PARAM_NAMES:
+                err = hz.rel_err(g.grad(c, 0, name), orc.grads[0][c][0][name])
+                assert err <= hz.TOL[cfg.dtype], (c, name, err)
