@@ -82,7 +82,8 @@ def lib():
         l.bp_prof_get.argtypes = [vp, ci, C.POINTER(C.c_double), C.POINTER(C.c_longlong),
                                   C.POINTER(C.c_double), C.POINTER(C.c_double)]
         l.bp_op_gemm.argtypes = [ci, ci, ci, ci, ci, ci, vp, ci, vp, ci, vp, ci, vp, vp, ci, vp]
-        l.bp_op_wgrad_group.argtypes = [ci, ci, ci, ci, ci, C.POINTER(vp), C.POINTER(vp), vp, ci, vp]
+        l.bp_op_wgrad_group.argtypes = [ci, ci, ci, ci, ci, C.POINTER(vp), C.POINTER(vp), vp, ci, vp,
+                                        C.c_size_t, vp]
         l.bp_op_layernorm_fwd.argtypes = [ci, ci, ci, vp, vp, vp, cf, vp, vp, vp, vp]
         l.bp_op_layernorm_bwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         l.bp_op_bias_gelu_fwd.argtypes = [ci, ci, ci, vp, vp, vp, vp]
@@ -242,11 +243,12 @@ def bp_op_gemm(dtype, a_t, b_t, M, N, K, A, lda, B, ldb, Cm, ldc, bias=None, res
                                    _ptr(bias), _ptr(residual), accumulate, stream))
 
 
-def bp_op_wgrad_group(dtype, M, N, T, X, dY, dW, overwrite=0, stream=None):
+def bp_op_wgrad_group(dtype, M, N, T, X, dY, dW, overwrite=0, workspace=None, workspace_elems=0, stream=None):
     n = len(X)
     xs = (C.c_void_p * n)(*[_ptr(x) for x in X])
     ys = (C.c_void_p * n)(*[_ptr(y) for y in dY])
-    return _check(lib().bp_op_wgrad_group(dtype, M, N, T, n, xs, ys, _ptr(dW), overwrite, stream))
+    return _check(lib().bp_op_wgrad_group(dtype, M, N, T, n, xs, ys, _ptr(dW), overwrite, _ptr(workspace),
+                                          workspace_elems, stream))
 
 
 def bp_op_layernorm_fwd(dtype, T, H, x, gamma, beta, eps, out, mean, rstd, stream=None):

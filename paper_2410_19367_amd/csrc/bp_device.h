@@ -68,4 +68,17 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// ---- GELU, tanh form (the approximation GPT-2 / Megatron use): g(x) = x/2 (1 + tanh(k (x + c x^3)))
+__device__ __forceinline__ float gelu_tanh_part(float x) {
+    // tanh(sqrt(2/pi) (x + 0.044715 x^3)) via exp; exact limits for large |x|
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    return 1.f - 2.f / (1.f + __expf(2.f * u));
+}
+__device__ __forceinline__ float gelu_value(float x) { return 0.5f * x * (1.f + gelu_tanh_part(x)); }
+__device__ __forceinline__ float gelu_slope(float x) {
+    const float t = gelu_tanh_part(x);
+    const float dudx = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
+    return 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * dudx;
+}
+
 }  // namespace bp

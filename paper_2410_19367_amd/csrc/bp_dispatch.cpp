@@ -22,6 +22,7 @@ hipError_t launch_gemm_per_segment(const GemmArgs& g, hipStream_t stream,
 
 hipError_t launch_gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
     if (g.nseg < 1 || g.nseg > kMaxGemmSegments || (g.nseg > 1 && !g.accumulate)) return hipErrorInvalidValue;
+    if (g.epi != EPI_NONE && !gemm_can_fuse_epilogue(dtype, g)) return hipErrorInvalidValue;
     if (dtype == BF16 && gemm_mfma_supported(g)) return launch_gemm_mfma(g, stream);
     if (g.nseg == 1) return launch_gemm_generic(dtype, g, stream);
     if (dtype == BF16)

@@ -77,6 +77,7 @@ struct Stage {
     std::vector<uint8_t> grad_clean[2];
     // Grouped weight gradients: per (direction, chunk) the micro-batches waiting for their group.
     int wgrad_group = 1;
+    bool fuse_gelu = true;               // GELU forward/backward inside the GEMM epilogues when possible
     std::vector<PendGroup> pend[2];
     std::vector<void*> pend_pool;                    // idle PendingMb buffers
     size_t q_dz = 0, q_du = 0, q_dy = 0, q_dqkv = 0, q_layer_bytes = 0;
@@ -98,6 +99,8 @@ struct Stage {
     float *ws_delta = nullptr, *ws_colsum[2] = {};
     float* ws_splitk = nullptr;          // split-K partials of main-stream GEMMs: 4 * T * H floats
     size_t ws_splitk_elems = 0;
+    float* ws_splitk_side = nullptr;     // the same for the weight-gradient GEMMs of the side stream
+    size_t ws_splitk_side_elems = 0;
 
     // key-padding lengths per micro-batch (device int32 [B])
     std::map<int, int32_t*> lens;

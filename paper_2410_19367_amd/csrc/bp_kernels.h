@@ -37,7 +37,18 @@ struct GemmArgs {
     int nseg = 1;
     const void* A_more[kMaxGemmSegments - 1] = {};
     const void* B_more[kMaxGemmSegments - 1] = {};
+    // Optional fused GELU epilogue (only with accumulate == 0 and no residual; honoured when
+    // gemm_can_fuse_epilogue() says so, callers run the separate kernels otherwise):
+    //   EPI_GELU_FWD : C = product (no bias), C2 = gelu(product + bias)
+    //   EPI_GELU_BWD : C = product * gelu'(U + bias), and colpart[r][n] = sum of C over rows
+    //                  32r .. 32r+31 (fp32, [M/32][N]), the partials of the bias gradient
+    int epi = 0;
+    void* C2 = nullptr;          // [M,N] ld = ldc
+    const void* U = nullptr;     // [M,N] ld = ldc
+    float* colpart = nullptr;
 };
+enum { EPI_NONE = 0, EPI_GELU_FWD = 1, EPI_GELU_BWD = 2 };
+bool gemm_can_fuse_epilogue(int dtype, const GemmArgs& g);
 
 // picks the MFMA kernel when the shape allows it, else the generic one
 hipError_t launch_gemm(int dtype, const GemmArgs& g, hipStream_t stream);

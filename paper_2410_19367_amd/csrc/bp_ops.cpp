@@ -36,7 +36,7 @@ int bp_op_gemm(int dtype, int a_t, int b_t, int M, int N, int K, const void* A, 
 }
 
 int bp_op_wgrad_group(int dtype, int M, int N, int T, int n, const void* const* X, const void* const* dY,
-                      float* dW, int overwrite, void* stream) {
+                      float* dW, int overwrite, float* workspace, size_t workspace_elems, void* stream) {
     if (check_dtype(dtype)) return BP_EINVAL;
     if (!X || !dY || !dW) return fail(BP_EINVAL, "null pointer");
     if (M <= 0 || N <= 0 || T <= 0) return fail(BP_EINVAL, "M, N, T must be positive");
@@ -50,6 +50,7 @@ int bp_op_wgrad_group(int dtype, int M, int N, int T, int n, const void* const* 
     g.a_t = 1; g.b_t = 0; g.accumulate = overwrite ? 2 : 1;
     g.nseg = n;
     for (int i = 1; i < n; ++i) { g.A_more[i - 1] = X[i]; g.B_more[i - 1] = dY[i]; }
+    if (workspace && workspace_elems) { g.split_ws = workspace; g.split_ws_elems = workspace_elems; }
     BP_OP_LAUNCH(bp::launch_gemm(dtype, g, (hipStream_t)stream));
 }
 

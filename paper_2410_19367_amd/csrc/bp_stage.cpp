@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 namespace bp {
@@ -144,6 +145,14 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     st->stream = (hipStream_t)opt.hip_stream;
     st->esz = dtype_size(st->dtype);
     st->wgrad_group = opt.wgrad_group ? opt.wgrad_group : std::min(4, std::max(1, 8192 / st->T));
+    // tuning switches for A/B measurements: BITPIPE_DISABLE is a bit mask, 1: GELU fused into the
+    // GEMM epilogues, 2: grouped weight gradients, 4: second stream
+    if (const char* dis = getenv("BITPIPE_DISABLE")) {
+        const long m = strtol(dis, nullptr, 0);
+        if (m & 1) st->fuse_gelu = false;
+        if (m & 2) st->wgrad_group = 1;
+        if (m & 4) st->overlap = false;
+    }
     st->pend[0].resize(st->n_chunks);
     st->pend[1].resize(st->n_chunks);
 
@@ -202,6 +211,9 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     if (!rc && st->dtype == BP_BF16) {
         st->ws_splitk_elems = (size_t)4 * st->T * st->H;
         rc = dev_alloc((void**)&st->ws_splitk, st->ws_splitk_elems * sizeof(float));
+        // weight gradients with few output tiles (H x H, or a narrow MLP) and a long token axis
+        st->ws_splitk_side_elems = std::min((size_t)4 * st->H * std::max(st->H, st->F), (size_t)64 << 20);
+        if (!rc) rc = dev_alloc((void**)&st->ws_splitk_side, st->ws_splitk_side_elems * sizeof(float));
     }
     if (!rc) rc = dev_alloc((void**)&st->ws_delta, (size_t)st->B * st->heads * st->S * sizeof(float));
     if (rc) { delete st; return rc; }
@@ -266,6 +278,7 @@ Stage::~Stage() {
     for (auto b : ws_dx) hipFree(b);
     hipFree(ws_h4);
     hipFree(ws_splitk);
+    hipFree(ws_splitk_side);
     hipFree(ws_delta);
     for (auto& kv : lens) hipFree(kv.second);
     hipFree(sched_act); hipFree(sched_grad); hipFree(sched_loss);
@@ -404,6 +417,10 @@ int Stage::wgrad_one(int dir, int chunk, int l, int k, const void* cur_x, const 
     g.a_t = 1; g.b_t = 0; g.accumulate = acc;
     g.nseg = n;
     for (int i = 1; i < n; ++i) { g.A_more[i - 1] = xs[i]; g.B_more[i - 1] = ys[i]; }
+    // all weight-gradient GEMMs run on one stream (the side stream, or the main one when the two
+    // are merged), one after the other, so they can share one split-K workspace
+    g.split_ws = ws_splitk_side;
+    g.split_ws_elems = ws_splitk_side_elems;
     Scoped sc(this, BP_K_GEMM, 2.0 * Mk[k] * Nk[k] * (double)T * n, 0);
     hipError_t e = launch_gemm(dtype, g, ss);
     if (e != hipSuccess) return fail(BP_EHIP, "weight-gradient GEMM: %s", hipGetErrorString(e));
@@ -602,12 +619,23 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
                                     (const float*)param(chunk, l, BP_LN2_B), eps, sb + s_m,
                                     (float*)(sb + s_mean2), (float*)(sb + s_rstd2), nullptr, stream));
         }
-        if ((rc = gemm(sb + s_m, H, 0, param_t(chunk, l, BP_W1), H, 1, sb + s_u, F, T, F, H, nullptr, nullptr, 0)))
-            return rc;
-        {
-            Scoped sc(this, BP_K_GELU_FWD, 0, 2.0 * T * F * esz);
-            BP_LAUNCH(launch_gelu_fwd(dtype, T, F, sb + s_u, (const float*)param(chunk, l, BP_B1),
-                                      sb + s_g, stream));
+        {   // u = m W1 and g = gelu(u + b1): one kernel when the GEMM can carry the activation
+            GemmArgs fg;
+            fg.A = sb + s_m; fg.B = param_t(chunk, l, BP_W1); fg.C = sb + s_u;
+            fg.bias = (const float*)param(chunk, l, BP_B1); fg.residual = nullptr;
+            fg.M = T; fg.N = F; fg.K = H; fg.lda = H; fg.ldb = H; fg.ldc = F;
+            fg.a_t = 0; fg.b_t = 1; fg.accumulate = 0;
+            fg.epi = EPI_GELU_FWD; fg.C2 = sb + s_g;
+            if (fuse_gelu && gemm_can_fuse_epilogue(dtype, fg)) {
+                Scoped sc(this, BP_K_GEMM, 2.0 * T * (double)F * H, 0);
+                BP_LAUNCH(launch_gemm(dtype, fg, stream));
+            } else {
+                if ((rc = gemm(sb + s_m, H, 0, param_t(chunk, l, BP_W1), H, 1, sb + s_u, F, T, F, H, nullptr,
+                               nullptr, 0))) return rc;
+                Scoped sc(this, BP_K_GELU_FWD, 0, 2.0 * T * F * esz);
+                BP_LAUNCH(launch_gelu_fwd(dtype, T, F, sb + s_u, (const float*)param(chunk, l, BP_B1),
+                                          sb + s_g, stream));
+            }
         }
         if ((rc = gemm(sb + s_g, F, 0, param_t(chunk, l, BP_W2), F, 1, z, H, T, H, F,
                        (const float*)param(chunk, l, BP_B2), sb + s_y, 0))) return rc;
@@ -706,11 +734,21 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         // z = y + g W2 + b2
         BP_HIP(hand_over(0));                                                                               // dz
         if (!defer && (rc = wgrad_one(dir, chunk, l, 0, sb + s_g, dz, acc, ss))) return rc;                 // dW2
-        if ((rc = gemm(dz, H, 0, P(BP_W2), H, 1, big1, F, T, F, H, nullptr, nullptr, 0))) return rc;        // dg
-        {   // du = dg * gelu'(u + b1); db1 partials (folded with the other column sums below)
-            Scoped sc(this, BP_K_GELU_BWD, 0, 3.0 * T * F * esz);
-            BP_LAUNCH(launch_gelu_bwd(dtype, T, F, big1, sb + s_u, (const float*)P(BP_B1), big1, nullptr, p_b1,
-                                      stream));
+        {   // du = (dz W2^T) * gelu'(u + b1) with the db1 partials: one kernel when the GEMM can carry it
+            GemmArgs bg;
+            bg.A = dz; bg.B = P(BP_W2); bg.C = big1; bg.bias = (const float*)P(BP_B1); bg.residual = nullptr;
+            bg.M = T; bg.N = F; bg.K = H; bg.lda = H; bg.ldb = H; bg.ldc = F;
+            bg.a_t = 0; bg.b_t = 1; bg.accumulate = 0;
+            bg.epi = EPI_GELU_BWD; bg.U = sb + s_u; bg.colpart = p_b1;
+            if (fuse_gelu && gemm_can_fuse_epilogue(dtype, bg)) {
+                Scoped sc(this, BP_K_GEMM, 2.0 * T * (double)F * H, 0);
+                BP_LAUNCH(launch_gemm(dtype, bg, stream));
+            } else {
+                if ((rc = gemm(dz, H, 0, P(BP_W2), H, 1, big1, F, T, F, H, nullptr, nullptr, 0))) return rc;    // dg
+                Scoped sc(this, BP_K_GELU_BWD, 0, 3.0 * T * F * esz);
+                BP_LAUNCH(launch_gelu_bwd(dtype, T, F, big1, sb + s_u, (const float*)P(BP_B1), big1, nullptr, p_b1,
+                                          stream));
+            }
         }
         BP_HIP(hand_over(1));                                                                               // du
         if (!defer && (rc = wgrad_one(dir, chunk, l, 1, sb + s_m, big1, acc, ss))) return rc;              // dW1

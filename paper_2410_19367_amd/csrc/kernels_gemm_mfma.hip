@@ -435,12 +435,25 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     const int n_base = n0 + wn * WTN;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+        const int m_base = m0 + wm * (BM / WM) + i * 32;
+        // EPI_GELU_BWD: the pre-activation values of this 32-row slab are requested before the
+        // accumulators are staged, so their latency overlaps the LDS round trip
+        constexpr int ELPR = WTN / 8, ERPI = rows_per_instr(ELPR), ENR = 32 / ERPI;
+        u32x4 upre[ENR];
+        if (g.epi == EPI_GELU_BWD && splits == 1) {
+#pragma unroll
+            for (int r = 0; r < ENR; ++r) {
+                const int row = r * ERPI + lane / ELPR;
+                if (ELPR * ERPI < 64 && lane >= ELPR * ERPI) continue;
+                upre[r] = *reinterpret_cast<const u32x4*>((const bf16_t*)g.U + (size_t)(m_base + row) * g.ldc +
+                                                          n_base + (lane % ELPR) * 8);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 ep[(8 * (v >> 2) + 4 * h + (v & 3)) * PITCH + j * 32 + (lane & 31)] = acc[i][j][v];
-        const int m_base = m0 + wm * (BM / WM) + i * 32;
         // rows per instruction: the largest power of two whose lanes fit in a wave (a 96-wide wave
         // tile leaves a quarter of the lanes idle here)
         if (splits > 1) {           // fp32 partial of this K slice, row-major [M][N]
@@ -472,22 +485,52 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
             float bias[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) bias[e] = g.bias ? g.bias[n_base + col + e] : 0.f;
+            float csum[8] = {0, 0, 0, 0, 0, 0, 0, 0};      // EPI_GELU_BWD: column sums of this slab
 #pragma unroll
             for (int r = 0; r < 32; r += RPI) {
                 const int row = r + lane / LPR;
                 if (LPR * RPI < 64 && lane >= LPR * RPI) continue;
                 const f32x4 v0 = *reinterpret_cast<const f32x4*>(ep + row * PITCH + col);
                 const f32x4 v1 = *reinterpret_cast<const f32x4*>(ep + row * PITCH + col + 4);
-                float o[8] = {v0[0] + bias[0], v0[1] + bias[1], v0[2] + bias[2], v0[3] + bias[3],
-                              v1[0] + bias[4], v1[1] + bias[5], v1[2] + bias[6], v1[3] + bias[7]};
+                float o[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
                 const size_t off = (size_t)(m_base + row) * g.ldc + n_base + col;
-                if (g.residual) {
-                    float rs[8];
-                    load8((const bf16_t*)g.residual + off, rs);
+                if (g.epi == EPI_GELU_FWD) {
+                    float act[8];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) o[e] += rs[e];
+                    for (int e = 0; e < 8; ++e) act[e] = gelu_value(o[e] + bias[e]);
+                    store8((bf16_t*)g.C + off, o);
+                    store8((bf16_t*)g.C2 + off, act);
+                } else if (g.epi == EPI_GELU_BWD) {
+                    const u32x4 ur = upre[r / RPI];
+                    const float u8[8] = {__uint_as_float(ur[0] << 16), __uint_as_float(ur[0] & 0xffff0000u),
+                                         __uint_as_float(ur[1] << 16), __uint_as_float(ur[1] & 0xffff0000u),
+                                         __uint_as_float(ur[2] << 16), __uint_as_float(ur[2] & 0xffff0000u),
+                                         __uint_as_float(ur[3] << 16), __uint_as_float(ur[3] & 0xffff0000u)};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        o[e] *= gelu_slope(u8[e] + bias[e]);
+                        csum[e] += o[e];
+                    }
+                    store8((bf16_t*)g.C + off, o);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] += bias[e];
+                    if (g.residual) {
+                        float rs[8];
+                        load8((const bf16_t*)g.residual + off, rs);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] += rs[e];
+                    }
+                    store8((bf16_t*)g.C + off, o);
                 }
-                store8((bf16_t*)g.C + off, o);
+            }
+            if (g.epi == EPI_GELU_BWD) {
+                // lanes l, l + LPR, l + 2 LPR, ... hold the same columns (LPR is a power of two here)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int o2 = LPR; o2 < 64; o2 <<= 1) csum[e] += __shfl_xor(csum[e], o2, 64);
+                if (lane < LPR) store8(g.colpart + (size_t)(m_base >> 5) * g.N + n_base + col, csum);
             }
         }
     }
@@ -602,11 +645,27 @@ bool gemm_mfma_supported(const GemmArgs& g) {
     return true;
 }
 
+static bool dma_path_ok(const GemmArgs& g) {
+    auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+    bool ok = g.M % 128 == 0 && g.N % 128 == 0 && g.K % BK == 0 && g.ldc % 8 == 0 && al16(g.C) &&
+              (!g.residual || al16(g.residual));
+    for (int i = 0; i + 1 < g.nseg; ++i) ok = ok && al16(g.A_more[i]) && al16(g.B_more[i]);
+    return ok;
+}
+
+bool gemm_can_fuse_epilogue(int dtype, const GemmArgs& g) {
+    auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+    if (dtype != BF16 || !gemm_mfma_supported(g) || !dma_path_ok(g)) return false;
+    if (g.accumulate || g.residual || g.nseg != 1 || !g.bias) return false;
+    if (g.epi == EPI_GELU_FWD) return g.C2 && al16(g.C2);
+    if (g.epi == EPI_GELU_BWD) return g.U && al16(g.U) && g.colpart && al16(g.colpart) && g.N % 8 == 0;
+    return false;
+}
+
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
-    bool aligned128 = g.M % 128 == 0 && g.N % 128 == 0 && g.K % BK == 0 && g.ldc % 8 == 0 &&
-                      al16(g.C) && (!g.residual || al16(g.residual));
-    for (int i = 0; i + 1 < g.nseg; ++i) aligned128 = aligned128 && al16(g.A_more[i]) && al16(g.B_more[i]);
+    const bool aligned128 = dma_path_ok(g);
+    if (g.epi != EPI_NONE && !gemm_can_fuse_epilogue(BF16, g)) return hipErrorInvalidValue;
     if (!aligned128) {
         if (g.nseg == 1) return launch_cfg<128, 128, 2, 2, true>(g, s);
         return launch_gemm_per_segment(g, s, [](const GemmArgs& h, hipStream_t st) {
@@ -620,12 +679,14 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     // for M = 2048, a quarter of the CUs idle) but 32 columns of 192 (256 tiles)
     auto fill = [](long t) { return t <= 0 ? 0.0 : (double)t / (double)(((t + 255) / 256) * 256); };
     const long t192 = (g.M % 256 == 0 && g.N % 192 == 0) ? (long)(g.M / 256) * (g.N / 192) : 0;
-    if (t192 >= 192 && 0.95 * fill(t192) > fill(t256)) return launch_dma<256, 192, 4, 2, 2>(g, s);
+    // (the fused GELU-backward epilogue folds column sums over power-of-two lane groups: not 96 wide)
+    if (g.epi == EPI_NONE && t192 >= 192 && 0.95 * fill(t192) > fill(t256))
+        return launch_dma<256, 192, 4, 2, 2>(g, s);
     if (t256 >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s);
     // Few output tiles but a long K: 256x256 tiles on K slices keep the operand traffic per flop
     // at the large-tile level (128x128 tiles are bound by the per-CU load path) and still give
     // every CU a block.  Slices stay >= 1024 deep so the partial traffic remains small.
-    if (t256 > 0 && g.split_ws) {
+    if (t256 > 0 && g.split_ws && g.epi == EPI_NONE) {
         int splits = (int)(256 / t256);
         if (splits > 4) splits = 4;
         const long k_total = (long)g.K * g.nseg;

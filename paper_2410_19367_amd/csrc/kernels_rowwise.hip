@@ -209,12 +209,6 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(ColsumBatch batch, in
 }
 
 // ------------------------------------------------------------------ bias + GELU
-__device__ __forceinline__ float gelu_tanh_part(float x) {
-    // tanh(sqrt(2/pi) (x + 0.044715 x^3)) via exp; exact limits for large |x|
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return 1.f - 2.f / (1.f + __expf(2.f * u));
-}
-
 template <typename T>
 __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T* __restrict__ u,
                                                        const float* __restrict__ bias,
@@ -229,7 +223,7 @@ __global__ __launch_bounds__(256) void gelu_fwd_kernel(const T* __restrict__ u,
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const float x = a[i] + b[i];
-            o[i] = 0.5f * x * (1.f + gelu_tanh_part(x));
+            o[i] = gelu_value(x);
         }
         store8(g + v * 8, o);
     }
@@ -271,10 +265,7 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const T* dg,   // may ali
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const float x = a[j][i] + b[i];
-                        const float t = gelu_tanh_part(x);
-                        const float dudx = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
-                        const float gp = 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * dudx;
-                        o[i] = d[j][i] * gp;
+                        o[i] = d[j][i] * gelu_slope(x);
                         acc[i] += o[i];
                     }
                     store8(du + (size_t)r * F + col, o);

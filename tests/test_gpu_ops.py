@@ -242,6 +242,9 @@ def test_attention_wide_score_range(B, S, heads, d, causal):
     (256, 256, 64, 4),         # one slice per segment
     (200, 264, 136, 3),        # ragged: one launch per segment
     (512, 768, 256, 1),
+    (2048, 2048, 1024, 4),     # with a workspace: 64 tiles x 4 token slices, one per segment
+    (2048, 2048, 2048, 2),     # with a workspace: 4 token slices, two per segment
+    (2048, 2048, 1536, 2),     # with a workspace: 3072 tokens -> 3 slices, boundaries inside segments
 ])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("overwrite", [0, 1])
@@ -261,7 +264,8 @@ def test_wgrad_group(M, N, T, n, dtype, overwrite):
     xd = [hz.to_dev(x, dtype) for x in xs]
     yd = [hz.to_dev(y, dtype) for y in ys]
     wd = _f32_dev(w0)
-    bp.bp_op_wgrad_group(dt, M, N, T, xd, yd, wd, overwrite)
+    ws = torch.empty(4 * M * N, device="cuda") if T >= 1024 else None
+    bp.bp_op_wgrad_group(dt, M, N, T, xd, yd, wd, overwrite, ws, 0 if ws is None else ws.numel())
     torch.cuda.synchronize()
     err = hz.rel_err(wd.cpu().numpy().astype(np.float64), ref)
     assert err <= (2e-3 if dtype == "bf16" else 1e-5), err
