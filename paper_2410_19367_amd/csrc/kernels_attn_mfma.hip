@@ -265,30 +265,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
 }
 
 // =====================================================================================
-// Backward, part 1: delta[q] = sum_d dO[q][d] * O[q][d]   (one wave per row)
-// =====================================================================================
-__global__ __launch_bounds__(256) void attn_delta_kernel(AttnArgs a, int D) {
-    const int lane = threadIdx.x & 63;
-    const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);     // over B*S*heads
-    const size_t total = (size_t)a.B * a.S * a.heads;
-    if (row >= total) return;
-    const int head = (int)(row % a.heads);
-    const size_t tok = row / a.heads;
-    const int H = a.heads * D;
-    const bf16_t* o = (const bf16_t*)a.ctx + tok * H + head * D;
-    const bf16_t* d_o = (const bf16_t*)a.dctx + tok * H + head * D;
-    float s = 0.f;
-    for (int c = lane * 2; c < D; c += 128)
-        s += (float)o[c] * (float)d_o[c] + (float)o[c + 1] * (float)d_o[c + 1];
-    s = wave_sum(s);
-    if (lane == 0) {
-        const size_t bb = tok / a.S, ss = tok % a.S;
-        a.delta[(bb * a.heads + head) * a.S + ss] = s;
-    }
-}
-
-// =====================================================================================
-// Backward, part 2: dQ.  Same decomposition as the forward (lane <-> query, two key halves):
+// Backward, part 1: dQ (and delta[q] = sum_d dO[q][d] O[q][d], kept for part 2).  Same decomposition as the forward (lane <-> query, two key halves):
 //   S^T = K Q^T, P^T = exp(S^T - lse), dP^T = V dO^T, dS^T = P^T (dP^T - delta),
 //   dQ^T (D x 32) += K^T dS^T         (K tile read plainly for S^T and transposed for dQ^T)
 // The two halves' partial dQ^T are added through LDS at the end.
@@ -325,7 +302,20 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
     }
     const size_t li = ((size_t)b * a.heads + head) * a.S + q_lane;
     const float lse2 = a.lse[li] * kLog2e;
-    const float delta = a.delta[li];
+    // delta[q] = sum_d dO[q][d] O[q][d]: each lane holds half of its query's dO row already; the
+    // value is also left in a.delta for the dK/dV kernel, which runs after this one
+    float delta = 0.f;
+    {
+        const bf16_t* ob = (const bf16_t*)a.ctx + ((size_t)b * a.S + q_lane) * H + head * D;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const bf16x8 of = *reinterpret_cast<const bf16x8*>(ob + 16 * s + 8 * h);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) delta += (float)of[e] * (float)dof[s][e];
+        }
+        delta += __shfl_xor(delta, 32, 64);
+        if (kh == 0 && h == 0) a.delta[li] = delta;
+    }
 
     f32x16 dq[DT];
 #pragma unroll
@@ -404,7 +394,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
 }
 
 // =====================================================================================
-// Backward, part 3: dK and dV.  Block = 4 waves = 2 groups of 32 keys x 2 halves of every
+// Backward, part 2: dK and dV.  Block = 4 waves = 2 groups of 32 keys x 2 halves of every
 // 64-query tile of Q / dO that streams by.
 //   S = Q K^T (lane <-> key), P = exp(S - lse[q]), dP = dO V^T, dS = P (dP - delta[q]),
 //   dV^T (D x 32 keys) += dO^T P,   dK^T (D x 32 keys) += Q^T dS
@@ -575,10 +565,7 @@ hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
     const float scale = 1.f / sqrtf((float)a.d);
-    const size_t rows = (size_t)a.B * a.S * a.heads;
-    hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a, a.d);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
     const dim3 grid((a.S / 64) * a.heads * a.B), block(256);
     if (a.d == 128) {
         const size_t smem = 2 * 2 * 64 * 128 * 2, smem2 = 2 * (2 * 64 * 128 * 2 + 512);

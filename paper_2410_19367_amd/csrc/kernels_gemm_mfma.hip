@@ -695,7 +695,8 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
             --splits;
         if (splits > 1 && t256 * splits >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s, splits);
     }
-    return launch_dma<128, 128, 2, 2, 2>(g, s);
+    // 8 waves (2 per SIMD) hide the LDS and load latencies better than 4 on these small tiles
+    return launch_dma<128, 128, 2, 4, 2>(g, s);
 }
 
 }  // namespace bp
