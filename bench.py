@@ -24,6 +24,12 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
+# Bytes that leave the L2s per GEMM launch (FETCH_SIZE + WRITE_SIZE of all GEMM kernels and their
+# split-K reduce kernels, scaled by the plain-copy calibration, divided by the number of GEMM
+# launches), from the hardware-counter passes over this same workload; counters cannot be read
+# from inside this process, so the figure is carried over from
+# profiles/stage_fwd_bwd_cfg1_pmc_counters.md.  Workloads without such a profile report null.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"cfg1_gpt_h2048": 223.5e6}
 
 
 def bench_schedule(args, cfg, bp, si, torch, np):
@@ -214,7 +220,7 @@ def main():
             "frac": round(gemm_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
             "avg_launch_ms": round(gemm_avg_ms, 5),
             "launches_per_step": gm["launches"] // args.steps,
-            "traffic": None,
+            "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
         },
         "kernels": kernels,
     }
