@@ -68,17 +68,21 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
-// ---- GELU, tanh form (the approximation GPT-2 / Megatron use): g(x) = x/2 (1 + tanh(k (x + c x^3)))
-__device__ __forceinline__ float gelu_tanh_part(float x) {
-    // tanh(sqrt(2/pi) (x + 0.044715 x^3)) via exp; exact limits for large |x|
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    return 1.f - 2.f / (1.f + __expf(2.f * u));
+// ---- GELU, tanh form (the approximation GPT-2 / Megatron use):
+//   g(x) = x/2 (1 + tanh(w)),  w = sqrt(2/pi) (x + 0.044715 x^3),  and  (1 + tanh(w))/2 = sigmoid(2w).
+// Written with the bare exp2 / reciprocal instructions: s = 1 / (1 + 2^(-2 w log2 e)) has the exact
+// limits 0 and 1 for large |x| (2^(+big) = inf, 1/inf = 0), so no range checks are needed.
+__device__ __forceinline__ float gelu_sigmoid(float x) {
+    const float x2 = x * x;
+    const float w2 = x * (-2.302208198f - 0.1029432397f * x2);    // -2 log2(e) sqrt(2/pi) (x + 0.044715 x^3)
+    return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(w2));
 }
-__device__ __forceinline__ float gelu_value(float x) { return 0.5f * x * (1.f + gelu_tanh_part(x)); }
+__device__ __forceinline__ float gelu_value(float x) { return x * gelu_sigmoid(x); }
+// g'(x) = s + x s (1 - s) 2 w'(x),  2 w'(x) = 2 sqrt(2/pi) (1 + 3 * 0.044715 x^2)
 __device__ __forceinline__ float gelu_slope(float x) {
-    const float t = gelu_tanh_part(x);
-    const float dudx = 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
-    return 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * dudx;
+    const float s = gelu_sigmoid(x);
+    const float dw2 = 1.5957691216f + 0.2140644488f * x * x;
+    return s + x * s * (1.f - s) * dw2;
 }
 
 }  // namespace bp
