@@ -93,7 +93,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=1, help="index into the baseline configs (1..3: stage configs; 4: whole V-schedule iteration)")
+    ap.add_argument("--config", type=int, default=1, help="index into synth_inputs.CONFIGS (1..3: baseline stage configs; 4: whole V-schedule iteration; 5, 6: stages of the paper's BERT-64 and GPT-96 at their own shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for FETCH_SIZE / WRITE_SIZE counters)")

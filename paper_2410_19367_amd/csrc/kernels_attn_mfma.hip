@@ -33,6 +33,20 @@ constexpr float kLn2 = 0.6931471805599453f;
 // bare v_exp_f32: arguments here are <= 8 and anything below -126 may flush to zero
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Head dimensions below the tile width D (any multiple of 8: 40 -> 64, 96 -> 128): the tile columns
+// at and beyond the real width dr are filled from this chunk of zeros and the register fragments
+// get zeros there, so the padded part contributes nothing; products that only touch padded columns
+// are skipped, and padded output columns are never stored.
+__device__ __attribute__((aligned(16))) unsigned int g_zero_chunk[4] = {0u, 0u, 0u, 0u};
+
+// 8 consecutive elements of a row starting at column `col`, zeros at and beyond column dr
+__device__ __forceinline__ bf16x8 load_frag(const bf16_t* row, int col, int dr) {
+    bf16x8 z;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = (bf16_t)0.f;
+    return col < dr ? *reinterpret_cast<const bf16x8*>(row + col) : z;
+}
+
 // ---- tile layout: [rows][D] bf16, 16-byte chunks XOR-swizzled by row
 template <int D> __device__ __forceinline__ int swz(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3))
@@ -43,11 +57,11 @@ template <int D> __device__ __forceinline__ int tile_off(int row, int chunk) {
 }
 
 // Direct global->LDS copy of a [64][D] tile by NW waves.  gbase points at (row 0, col 0) of the
-// tile, ld is the row pitch in elements.  Rows >= rows_valid are fetched from row 0 instead
+// tile, ld is the row pitch in elements, dr the real row width.  Rows >= rows_valid are fetched from row 0 instead
 // (their values are masked or discarded by the caller), which keeps every access in bounds.
 template <int D, int NW>
 __device__ __forceinline__ void dma_tile(const bf16_t* gbase, int ld, char* lds, int wave, int lane,
-                                         int rows_valid) {
+                                         int rows_valid, int dr) {
     constexpr int CPR = D / 8;              // chunks per row
     constexpr int NI = 64 * CPR / 64 / NW;  // wave instructions per wave
 #pragma unroll
@@ -57,8 +71,9 @@ __device__ __forceinline__ void dma_tile(const bf16_t* gbase, int ld, char* lds,
         int row = P / CPR;
         const int c = (P % CPR) ^ swz<D>(row);
         if (row >= rows_valid) row = 0;
+        const bf16_t* src = c * 8 < dr ? gbase + (size_t)row * ld + c * 8 : (const bf16_t*)g_zero_chunk;
         __builtin_amdgcn_global_load_lds(
-            (const void __attribute__((address_space(1)))*)(gbase + (size_t)row * ld + c * 8),
+            (const void __attribute__((address_space(1)))*)src,
             (void __attribute__((address_space(3)))*)(lds + j * 1024), 16, 0, 0);
     }
 }
@@ -121,7 +136,7 @@ __device__ __forceinline__ void block_coords(int nblk, int heads, bool causal, b
 // Forward.  Block = 4 waves = 2 groups of 32 queries x 2 halves of every 64-key tile; each wave
 // keeps its own online-softmax state and the two halves are merged through LDS at the end.
 // =====================================================================================
-template <int D>
+template <int D, bool PAD>
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float scale) {
     constexpr int NW = 4, KS = D / 16, DT = D / 32;
     constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE;   // K then V
@@ -133,8 +148,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
     const int h = lane >> 5;
     int qblk, head, b;
     block_coords(a.S / 64, a.heads, a.causal != 0, true, qblk, head, b);
-    const int H = a.heads * D, ld = 3 * H;
-    const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * D;
+    const int dr = PAD ? a.d : D;             // real head dimension; the guards below fold away when it equals D
+    const int H = a.heads * dr, ld = 3 * H;
+    const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * dr;
     const bf16_t* kbase = qkv + H;
     const bf16_t* vbase = qkv + 2 * H;
     const int q_wave = qblk * 64 + qg * 32;
@@ -147,7 +163,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
     bf16x8 qf[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s)
-        qf[s] = *reinterpret_cast<const bf16x8*>(qkv + (size_t)q_lane * ld + 16 * s + 8 * h);
+        qf[s] = load_frag(qkv + (size_t)q_lane * ld, 16 * s + 8 * h, dr);
 
     f32x16 ot[DT];
 #pragma unroll
@@ -156,8 +172,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
         for (int v = 0; v < 16; ++v) ot[t][v] = 0.f;
     float m = -INFINITY, lsum = 0.f;
 
-    dma_tile<D, NW>(kbase, ld, smem, wave, lane, a.S);
-    dma_tile<D, NW>(vbase, ld, smem + TILE, wave, lane, a.S);
+    dma_tile<D, NW>(kbase, ld, smem, wave, lane, a.S, dr);
+    dma_tile<D, NW>(vbase, ld, smem + TILE, wave, lane, a.S, dr);
 
     for (int t = 0; t < nt; ++t) {
         const int k0 = t * 64;
@@ -166,8 +182,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
         if (t + 1 < nt) {
             char* st = smem + ((t + 1) & 1) * STAGE;
             const int rows = a.S - (k0 + 64);
-            dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows);
-            dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows);
+            dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows, dr);
+            dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows, dr);
         }
         const int kw = k0 + 32 * kh;                    // first key of this wave's half
         if ((a.causal && kw > q_wave + 31) || kw >= klen) continue;     // nothing unmasked for this wave
@@ -180,7 +196,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
         for (int v = 0; v < 16; ++v) st2[v] = 0.f;
 #pragma unroll
         for (int s = 0; s < KS; ++s)
-            st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, 32 * kh, s, lane), qf[s], st2, 0, 0, 0);
+            if (16 * s < dr)
+                st2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, 32 * kh, s, lane), qf[s], st2, 0, 0, 0);
         const bool need_mask = (a.causal && kw + 31 > q_wave) || (kw + 32 > klen);
         float mx = -INFINITY;
 #pragma unroll
@@ -223,8 +240,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
             const bf16x8 pb = acc_to_b(st2, s2);
 #pragma unroll
             for (int t2 = 0; t2 < DT; ++t2)
-                ot[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    frag_cols<D>(sv, 32 * kh + 16 * s2, t2 * 32, lane), pb, ot[t2], 0, 0, 0);
+                if (32 * t2 < dr)
+                    ot[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        frag_cols<D>(sv, 32 * kh + 16 * s2, t2 * 32, lane), pb, ot[t2], 0, 0, 0);
         }
     }
 
@@ -247,7 +265,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
     const float a0 = fast_exp2(m - mm), a1 = fast_exp2(m1 - mm);
     l = l * a0 + l1 * a1;
     const float inv = 1.f / l;
-    bf16_t* out = (bf16_t*)a.ctx + ((size_t)b * a.S + q_lane) * H + head * D;
+    bf16_t* out = (bf16_t*)a.ctx + ((size_t)b * a.S + q_lane) * H + head * dr;
 #pragma unroll
     for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
@@ -259,7 +277,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
             uint2 pk;
             pk.x = pack_bf16x2(o4[0], o4[1]);
             pk.y = pack_bf16x2(o4[2], o4[3]);
-            *reinterpret_cast<uint2*>(out + t2 * 32 + 8 * g + 4 * h) = pk;
+            if (t2 * 32 + 8 * g + 4 * h < dr) *reinterpret_cast<uint2*>(out + t2 * 32 + 8 * g + 4 * h) = pk;
         }
     if (h == 0) a.lse[((size_t)b * a.heads + head) * a.S + q_lane] = (mm + log2f(l)) * kLn2;
 }
@@ -270,7 +288,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
 //   dQ^T (D x 32) += K^T dS^T         (K tile read plainly for S^T and transposed for dQ^T)
 // The two halves' partial dQ^T are added through LDS at the end.
 // =====================================================================================
-template <int D>
+template <int D, bool PAD>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, float scale) {
     constexpr int NW = 4, KS = D / 16, DT = D / 32;
     constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE;
@@ -282,8 +300,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
     const int h = lane >> 5;
     int qblk, head, b;
     block_coords(a.S / 64, a.heads, a.causal != 0, true, qblk, head, b);
-    const int H = a.heads * D, ld = 3 * H;
-    const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * D;
+    const int dr = PAD ? a.d : D;             // real head dimension; the guards below fold away when it equals D
+    const int H = a.heads * dr, ld = 3 * H;
+    const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * dr;
     const bf16_t* kbase = qkv + H;
     const bf16_t* vbase = qkv + 2 * H;
     const int q_wave = qblk * 64 + qg * 32;
@@ -293,12 +312,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
     const int nt = (kend + 63) / 64;
     const float c = scale * kLog2e;
 
-    const bf16_t* dob = (const bf16_t*)a.dctx + ((size_t)b * a.S + q_lane) * H + head * D;
+    const bf16_t* dob = (const bf16_t*)a.dctx + ((size_t)b * a.S + q_lane) * H + head * dr;
     bf16x8 qf[KS], dof[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        qf[s] = *reinterpret_cast<const bf16x8*>(qkv + (size_t)q_lane * ld + 16 * s + 8 * h);
-        dof[s] = *reinterpret_cast<const bf16x8*>(dob + 16 * s + 8 * h);
+        qf[s] = load_frag(qkv + (size_t)q_lane * ld, 16 * s + 8 * h, dr);
+        dof[s] = load_frag(dob, 16 * s + 8 * h, dr);
     }
     const size_t li = ((size_t)b * a.heads + head) * a.S + q_lane;
     const float lse2 = a.lse[li] * kLog2e;
@@ -306,10 +325,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
     // value is also left in a.delta for the dK/dV kernel, which runs after this one
     float delta = 0.f;
     {
-        const bf16_t* ob = (const bf16_t*)a.ctx + ((size_t)b * a.S + q_lane) * H + head * D;
+        const bf16_t* ob = (const bf16_t*)a.ctx + ((size_t)b * a.S + q_lane) * H + head * dr;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            const bf16x8 of = *reinterpret_cast<const bf16x8*>(ob + 16 * s + 8 * h);
+            const bf16x8 of = load_frag(ob, 16 * s + 8 * h, dr);
 #pragma unroll
             for (int e = 0; e < 8; ++e) delta += (float)of[e] * (float)dof[s][e];
         }
@@ -323,8 +342,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
 #pragma unroll
         for (int v = 0; v < 16; ++v) dq[t][v] = 0.f;
 
-    dma_tile<D, NW>(kbase, ld, smem, wave, lane, a.S);
-    dma_tile<D, NW>(vbase, ld, smem + TILE, wave, lane, a.S);
+    dma_tile<D, NW>(kbase, ld, smem, wave, lane, a.S, dr);
+    dma_tile<D, NW>(vbase, ld, smem + TILE, wave, lane, a.S, dr);
 
     for (int t = 0; t < nt; ++t) {
         const int k0 = t * 64;
@@ -333,8 +352,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
         if (t + 1 < nt) {
             char* st = smem + ((t + 1) & 1) * STAGE;
             const int rows = a.S - (k0 + 64);
-            dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows);
-            dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows);
+            dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows, dr);
+            dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows, dr);
         }
         const int kw = k0 + 32 * kh;
         if ((a.causal && kw > q_wave + 31) || kw >= klen) continue;
@@ -346,6 +365,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
         for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
+            if (16 * s >= dr) continue;
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sk, 32 * kh, s, lane), qf[s], sacc, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sv, 32 * kh, s, lane), dof[s], dp, 0, 0, 0);
         }
@@ -363,8 +383,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
             const bf16x8 db = acc_to_b(dp, s2);
 #pragma unroll
             for (int t2 = 0; t2 < DT; ++t2)
-                dq[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    frag_cols<D>(sk, 32 * kh + 16 * s2, t2 * 32, lane), db, dq[t2], 0, 0, 0);
+                if (32 * t2 < dr)
+                    dq[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        frag_cols<D>(sk, 32 * kh + 16 * s2, t2 * 32, lane), db, dq[t2], 0, 0, 0);
         }
     }
     __syncthreads();
@@ -377,7 +398,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
     }
     __syncthreads();
     if (kh == 1) return;
-    bf16_t* out = (bf16_t*)a.dqkv + ((size_t)b * a.S + q_lane) * ld + head * D;
+    bf16_t* out = (bf16_t*)a.dqkv + ((size_t)b * a.S + q_lane) * ld + head * dr;
 #pragma unroll
     for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
@@ -389,7 +410,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
             uint2 pk;
             pk.x = pack_bf16x2(o4[0], o4[1]);
             pk.y = pack_bf16x2(o4[2], o4[3]);
-            *reinterpret_cast<uint2*>(out + t2 * 32 + 8 * g + 4 * h) = pk;
+            if (t2 * 32 + 8 * g + 4 * h < dr) *reinterpret_cast<uint2*>(out + t2 * 32 + 8 * g + 4 * h) = pk;
         }
 }
 
@@ -400,7 +421,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
 //   dV^T (D x 32 keys) += dO^T P,   dK^T (D x 32 keys) += Q^T dS
 // The two query halves' partial sums are added through LDS at the end.
 // =====================================================================================
-template <int D>
+template <int D, bool PAD>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, float scale) {
     constexpr int NW = 4, KS = D / 16, DT = D / 32;
     constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE + 512;   // Q, dO, then lse[64], delta[64]
@@ -412,13 +433,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
     const int h = lane >> 5;
     int kblk, head, b;
     block_coords(a.S / 64, a.heads, a.causal != 0, false, kblk, head, b);   // key block 0 is the heaviest
-    const int H = a.heads * D, ld = 3 * H;
-    const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * D;
-    const bf16_t* dobase = (const bf16_t*)a.dctx + (size_t)b * a.S * H + head * D;
+    const int dr = PAD ? a.d : D;             // real head dimension; the guards below fold away when it equals D
+    const int H = a.heads * dr, ld = 3 * H;
+    const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * dr;
+    const bf16_t* dobase = (const bf16_t*)a.dctx + (size_t)b * a.S * H + head * dr;
     const int k_wave = kblk * 64 + kg * 32;
     const int k_lane = k_wave + (lane & 31);
     const int klen = a.causal ? a.S : (a.lens ? a.lens[b] : a.S);
-    bf16_t* dk_out = (bf16_t*)a.dqkv + ((size_t)b * a.S + k_lane) * ld + H + head * D;
+    bf16_t* dk_out = (bf16_t*)a.dqkv + ((size_t)b * a.S + k_lane) * ld + H + head * dr;
     bf16_t* dv_out = dk_out + H;
     if (kblk * 64 >= klen) {      // the whole block of keys is padding: no query attends it
         if (qh == 0) {
@@ -427,6 +449,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
             for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
+                    if (t2 * 32 + 8 * g + 4 * h >= dr) continue;
                     *reinterpret_cast<uint2*>(dk_out + t2 * 32 + 8 * g + 4 * h) = z;
                     *reinterpret_cast<uint2*>(dv_out + t2 * 32 + 8 * g + 4 * h) = z;
                 }
@@ -440,8 +463,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
     bf16x8 kf[KS], vf[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-        kf[s] = *reinterpret_cast<const bf16x8*>(qkv + H + (size_t)k_lane * ld + 16 * s + 8 * h);
-        vf[s] = *reinterpret_cast<const bf16x8*>(qkv + 2 * H + (size_t)k_lane * ld + 16 * s + 8 * h);
+        kf[s] = load_frag(qkv + H + (size_t)k_lane * ld, 16 * s + 8 * h, dr);
+        vf[s] = load_frag(qkv + 2 * H + (size_t)k_lane * ld, 16 * s + 8 * h, dr);
     }
     f32x16 dk[DT], dv[DT];
 #pragma unroll
@@ -454,8 +477,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
 
     auto load_stage = [&](int t, char* st) {
         const int q0 = t * 64;
-        dma_tile<D, NW>(qkv + (size_t)q0 * ld, ld, st, wave, lane, a.S - q0);
-        dma_tile<D, NW>(dobase + (size_t)q0 * H, H, st + TILE, wave, lane, a.S - q0);
+        dma_tile<D, NW>(qkv + (size_t)q0 * ld, ld, st, wave, lane, a.S - q0, dr);
+        dma_tile<D, NW>(dobase + (size_t)q0 * H, H, st + TILE, wave, lane, a.S - q0, dr);
         if (threadIdx.x < 64) ((float*)(st + 2 * TILE))[threadIdx.x] = lse[q0 + threadIdx.x] * kLog2e;
         else if (threadIdx.x < 128) ((float*)(st + 2 * TILE))[threadIdx.x] = dlt[q0 + threadIdx.x - 64];
     };
@@ -478,6 +501,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
         for (int v = 0; v < 16; ++v) { sacc[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
+            if (16 * s >= dr) continue;
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sq, 32 * qh, s, lane), kf[s], sacc, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sdo, 32 * qh, s, lane), vf[s], dp, 0, 0, 0);
         }
@@ -496,6 +520,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
             const bf16x8 db = acc_to_b(dp, s2);
 #pragma unroll
             for (int t2 = 0; t2 < DT; ++t2) {
+                if (32 * t2 >= dr) continue;
                 dv[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     frag_cols<D>(sdo, 32 * qh + 16 * s2, t2 * 32, lane), pb, dv[t2], 0, 0, 0);
                 dk[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
@@ -526,6 +551,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
                 k4[e] = (dk[t2][4 * g + e] + xo[(t2 * 16 + 4 * g + e) * 64 + lane]) * scale;
                 v4[e] = dv[t2][4 * g + e] + xo[((DT + t2) * 16 + 4 * g + e) * 64 + lane];
             }
+            if (t2 * 32 + 8 * g + 4 * h >= dr) continue;
             uint2 pk;
             pk.x = pack_bf16x2(k4[0], k4[1]);
             pk.y = pack_bf16x2(k4[2], k4[3]);
@@ -539,7 +565,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
 // ---- host side
 bool attn_mfma_supported(const AttnArgs& a) {
     auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
-    if (a.d != 64 && a.d != 128) return false;
+    if (a.d % 8 || a.d < 8 || a.d > 128) return false;      // tile width 64 or 128, narrower heads are padded
     if (a.S % 64) return false;
     return al16(a.qkv) && al16(a.ctx) && (!a.dctx || al16(a.dctx)) && (!a.dqkv || al16(a.dqkv));
 }
@@ -550,38 +576,48 @@ static hipError_t set_smem(K kern, size_t smem) {
     return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
 }
 
-hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
+template <int D, bool PAD>
+static hipError_t launch_fwd_t(const AttnArgs& a, hipStream_t s) {
     const float scale = 1.f / sqrtf((float)a.d);
     const dim3 grid((a.S / 64) * a.heads * a.B), block(256);
-    if (a.d == 128) {
-        const size_t smem = 2 * 2 * 64 * 128 * 2;
-        hipLaunchKernelGGL((attn_fwd_mfma_kernel<128>), grid, block, smem, s, a, scale);
-    } else {
-        const size_t smem = 2 * 2 * 64 * 64 * 2;
-        hipLaunchKernelGGL((attn_fwd_mfma_kernel<64>), grid, block, smem, s, a, scale);
+    const size_t smem = 2 * 2 * 64 * D * 2;
+    static bool set = false;
+    if (!set) {
+        hipError_t e = set_smem(attn_fwd_mfma_kernel<D, PAD>, smem);
+        if (e != hipSuccess) return e;
+        set = true;
     }
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, PAD>), grid, block, smem, s, a, scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
+    if (a.d == 128) return launch_fwd_t<128, false>(a, s);
+    if (a.d == 64) return launch_fwd_t<64, false>(a, s);
+    return a.d > 64 ? launch_fwd_t<128, true>(a, s) : launch_fwd_t<64, true>(a, s);
+}
+
+template <int D, bool PAD>
+static hipError_t launch_bwd_t(const AttnArgs& a, hipStream_t s) {
+    const float scale = 1.f / sqrtf((float)a.d);
+    const dim3 grid((a.S / 64) * a.heads * a.B), block(256);
+    const size_t smem = 2 * 2 * 64 * D * 2, smem2 = 2 * (2 * 64 * D * 2 + 512);
+    static bool set = false;
+    if (!set) {
+        hipError_t e = set_smem(attn_bwd_dq_mfma_kernel<D, PAD>, smem);
+        if (e == hipSuccess) e = set_smem(attn_bwd_dkv_mfma_kernel<D, PAD>, smem2);
+        if (e != hipSuccess) return e;
+        set = true;
+    }
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, PAD>), grid, block, smem, s, a, scale);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, PAD>), grid, block, smem2, s, a, scale);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
-    const float scale = 1.f / sqrtf((float)a.d);
-    hipError_t e = hipSuccess;
-    const dim3 grid((a.S / 64) * a.heads * a.B), block(256);
-    if (a.d == 128) {
-        const size_t smem = 2 * 2 * 64 * 128 * 2, smem2 = 2 * (2 * 64 * 128 * 2 + 512);
-        static bool set = false;
-        if (!set) {
-            if ((e = set_smem(attn_bwd_dkv_mfma_kernel<128>, smem2)) != hipSuccess) return e;
-            set = true;
-        }
-        hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<128>), grid, block, smem, s, a, scale);
-        hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<128>), grid, block, smem2, s, a, scale);
-    } else {
-        const size_t smem = 2 * 2 * 64 * 64 * 2, smem2 = 2 * (2 * 64 * 64 * 2 + 512);
-        hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<64>), grid, block, smem, s, a, scale);
-        hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<64>), grid, block, smem2, s, a, scale);
-    }
-    return hipGetLastError();
+    if (a.d == 128) return launch_bwd_t<128, false>(a, s);
+    if (a.d == 64) return launch_bwd_t<64, false>(a, s);
+    return a.d > 64 ? launch_bwd_t<128, true>(a, s) : launch_bwd_t<64, true>(a, s);
 }
 
 }  // namespace bp

@@ -134,13 +134,17 @@ class StageConfig:
         return self.layers * (gemm + attn)
 
 
-# The five workloads of the baseline file, in its order.
+# The five workloads of the baseline file, in its order, followed by one stage of each of the
+# paper's two large models at their own shapes (Table 3: BERT-64 with 64 heads of width 40,
+# GPT-96 with 32 heads of width 96; micro-batch sizes of Section 4.2).
 CONFIGS = (
     StageConfig("cfg0_tiny_gpt_f32", 2, 128, 2, 64, 2, True, "f32", 4),
     StageConfig("cfg1_gpt_h2048", 4, 2048, 16, 2048, 1, True, "bf16", 8),
     StageConfig("cfg2_bert_h1024", 6, 1024, 16, 512, 8, False, "bf16", 8, len_lo=256, len_hi=512),
     StageConfig("cfg3_gpt_h5120", 2, 5120, 40, 2048, 2, True, "bf16", 16),
     StageConfig("cfg4_vsched_h1024", 2, 1024, 16, 1024, 1, True, "bf16", 8, n_chunks=8),
+    StageConfig("cfg5_bert64_stage_h2560_d40", 4, 2560, 64, 512, 4, False, "bf16", 8, len_lo=256, len_hi=512),
+    StageConfig("cfg6_gpt96_stage_h3072_d96", 6, 3072, 32, 1024, 1, True, "bf16", 8),
 )
 
 

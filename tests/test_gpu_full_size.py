@@ -42,3 +42,20 @@ def test_cfg4_v_schedule_full():
     H 1024, S 1024: loss and every accumulated gradient against the non-pipelined full-batch oracle."""
     loss, grads, worst = _run_iteration(si.CONFIGS[4], 4)
     print("cfg4 loss", loss, "worst grad err", f"{worst:.2e}", flush=True)
+
+
+def test_cfg5_bert64_stage_d40_two_layers():
+    """One stage of the paper's BERT-64 (Table 3) at its own width: H 2560, 64 heads of width 40
+    (padded to 64 inside the attention kernels), S 512, B 4, key padding; two of the stage's
+    four layers (the others repeat the same kernels on the same shapes)."""
+    cfg = si.scaled(si.CONFIGS[5], name="cfg5_two_layers", layers=2)
+    errs = hz.run_fwd_bwd_parity(cfg, n_micro=1)
+    _report("cfg5", errs)
+
+
+def test_cfg6_gpt96_stage_d96_two_layers():
+    """One stage of the paper's GPT-96 (Table 3): H 3072, 32 heads of width 96 (padded to 128),
+    S 1024, B 1, causal; two of its six layers."""
+    cfg = si.scaled(si.CONFIGS[6], name="cfg6_two_layers", layers=2)
+    errs = hz.run_fwd_bwd_parity(cfg, n_micro=2)
+    _report("cfg6", errs)

@@ -148,6 +148,15 @@ ATTN_CASES = [
     (2, 192, 2, 64, True, None),
     (1, 320, 3, 128, False, [200]),
     (2, 64, 2, 128, True, None),
+    # head widths below the tile width (padded inside the MFMA kernels): the paper's 40 and 96, and others
+    (2, 128, 4, 40, False, [128, 77]),
+    (1, 256, 2, 96, True, None),
+    (2, 192, 2, 40, True, None),
+    (1, 128, 3, 96, False, [100]),
+    (1, 192, 2, 32, True, None),
+    (1, 128, 2, 112, False, None),
+    (1, 128, 2, 48, True, None),
+    (1, 64, 2, 8, True, None),
 ]
 
 

@@ -20,6 +20,9 @@ def test_cfg0_tiny_gpt_fp32_full():
     ("bert_d64_padded", dict(layers=2, hidden=256, heads=4, seq=160, microbatch=3, causal=False,
                              len_lo=40, len_hi=160)),
     ("bert_full_len", dict(layers=1, hidden=128, heads=2, seq=96, microbatch=2, causal=False)),
+    ("bert_d40_padded", dict(layers=2, hidden=320, heads=8, seq=128, microbatch=2, causal=False,
+                             len_lo=40, len_hi=128)),
+    ("gpt_d96", dict(layers=2, hidden=384, heads=4, seq=192, microbatch=1, causal=True)),
 ])
 def test_small_bf16_stages(name, kw):
     cfg = si.scaled(si.CONFIGS[1], name="small_" + name, n_micro=2, **kw)
