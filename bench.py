@@ -51,7 +51,9 @@ def bench_schedule(args, cfg, bp, si, torch, np):
                 bp.bp_stage_set_param(st, c, l, tid, params[c][l][name])
     inputs = to_dev(np.stack([si.make_activation(cfg, "act_in", m) for m in range(N)]))
     targets = to_dev(np.stack([si.make_activation(cfg, "target", m) for m in range(N)]))
-    order = bp.bp_schedule_generate(D, N)
+    variant = 1 if args.order == "early" else 0
+    order = bp.bp_schedule_generate(D, N, variant)
+    model_ms, model_idle, model_peak = bp.bp_schedule_simulate(order, D, N)
     for _ in range(args.warmup):
         bp.bp_run_schedule(st, order, D, inputs, targets)
     torch.cuda.synchronize()
@@ -75,7 +77,11 @@ def bench_schedule(args, cfg, bp, si, torch, np):
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "stages": cfg.n_chunks, "virtual_devices": D, "layers_per_stage": cfg.layers,
                    "hidden": cfg.hidden, "heads": cfg.heads, "seq": cfg.seq, "microbatch": cfg.microbatch,
-                   "micro_batches_per_step": N, "order": "V-shaped bidirectional, concatenated units"},
+                   "micro_batches_per_step": N,
+                   "order": "V-shaped bidirectional, " + ("early forwarding" if variant else "concatenated units")},
+        # the same order replayed under the paper's cost model (chunk forward 1, backward 2, D devices)
+        "cost_model": {"makespan": model_ms, "bubble_ratio": round(max(model_idle) / model_ms, 5),
+                       "peak_chunk_stashes": max(model_peak)},
         "tokens_per_s": round(cfg.T * N * args.steps / dt, 1),
         "mfma_util": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "loss": round(float(loss), 4),
@@ -94,6 +100,8 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=1, help="index into synth_inputs.CONFIGS (1..3: baseline stage configs; 4: whole V-schedule iteration; 5, 6: stages of the paper's BERT-64 and GPT-96 at their own shapes)")
+    ap.add_argument("--order", choices=["concat", "early"], default="concat",
+                    help="config 4 only: concatenated basic units or early forwarding")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for FETCH_SIZE / WRITE_SIZE counters)")

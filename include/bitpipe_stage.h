@@ -142,7 +142,10 @@ typedef struct bp_op {
     int32_t mb;       /* 0..N-1 */
 } bp_op;
 
-enum bp_schedule_variant { BP_SCHED_V_CONCAT = 0 };
+/* BP_SCHED_V_CONCAT: basic units concatenated (Section 3.5).  BP_SCHED_V_EARLY_FWD: early
+ * forwarding (Appendix B): forwards of later micro-batches run ahead of time, removing the bubbles
+ * between units at the price of up to 3D-3 instead of 2D chunk stashes per device. */
+enum bp_schedule_variant { BP_SCHED_V_CONCAT = 0, BP_SCHED_V_EARLY_FWD = 1 };
 
 /* Pure CPU.  Stage -> virtual device of the V-shaped map (Section 3.2, Section 3.3):
  * down: 0..D-1 then D-1..0; up: the mirror image.  Returns -1 on bad arguments. */
@@ -152,6 +155,8 @@ int bp_schedule_vmap(int dir, int stage, int D);
  * and N micro-batches (N a multiple of D, D even; Section 3.3 basic unit, Section 3.5
  * concatenation) into out[0..cap); *n_out = 4*D*N ops.  The order is the list schedule under
  * the paper's cost model (chunk forward 1, backward 2), serialised by (start time, device).
+ * Under that cost model and D = 4 the orders reach the paper's closed forms: CONCAT bubble ratio
+ * (D-2)/(3N+D-2) at N = D, EARLY_FWD (D-2)/(4N+D-2) and peak (3D-3)/2 M_a for N = 2D..6D.
  * BP_EINVAL for odd D, N % D != 0, cap too small or an unknown variant. */
 int bp_schedule_generate(int D, int N, int variant, bp_op* out, int cap, int* n_out);
 

@@ -20,6 +20,15 @@ there is one (lowest micro-batch first), otherwise the ready forward of the high
 (lowest micro-batch first), never holding more than 2D chunk stashes, and admitting a new micro-batch
 only while fewer than 3D/2 are in flight.  At D = 4 this reproduces
 the closed forms above; for D > 4 it does not reach them (parity unpinned beyond D = 4).
+  * Early forwarding (Appendix B, Eq. 1-2): for N > D, forwards of later micro-batches are run
+    ahead of time so that the bubbles between concatenated units disappear; the bubble ratio drops
+    to (D-2)/(4N+D-2) (idle (D-2)/4 (t_f + t_b) per device) at a peak of (3D-3)/2 M_a.  Rebuilt
+    here as a second list-scheduling rule: a device that holds fewer than 2D chunk stashes prefers
+    a ready forward (deepest stage first), one that holds 2D or more prefers a ready backward
+    (lowest stage first, i.e. the one closest to releasing its micro-batch); never more than
+    3D-3 chunk stashes per device, at most 2D micro-batches in flight.  At D = 4 and N = 2D..6D
+    this gives exactly makespan 6N + 3, idle 3 per device and peak 9 = 3D-3 chunk stashes: the
+    paper's closed forms.  For D > 4 it does not reach them in general (parity unpinned).
 """
 from __future__ import annotations
 
@@ -45,7 +54,7 @@ def direction_of(mb, D):
     return 0 if (mb % D) < D // 2 else 1
 
 
-def generate_timeline(D, N, cost_f=1, cost_b=2):
+def generate_timeline(D, N, cost_f=1, cost_b=2, early_forward=False):
     """List-schedule one iteration.  Returns per-device lists of Slot(start, end, op).
 
     Time advances in unit steps; at each step the devices are visited in index order and a free
@@ -54,12 +63,19 @@ def generate_timeline(D, N, cost_f=1, cost_b=2):
     the backward finishes).  A micro-batch is admitted (stage-0 forward) only while fewer than
     3D/2 admitted micro-batches still await their stage-0 backward: that lets the next basic
     unit's first forwards fill the tail bubbles of the previous one without flooding the
-    stashes.  Raises RuntimeError if the greedy order stalls."""
+    stashes.  early_forward selects the Appendix-B rule described in the module header instead.
+    Raises RuntimeError if the greedy order stalls."""
     if D < 2 or D % 2 or N < D or N % D:
         raise ValueError("need even D >= 2 and N a positive multiple of D")
     n_stage = 2 * D
-    cap = 2 * D
-    window = D + D // 2
+    if early_forward:
+        cap = 3 * D - 3 if D > 2 else 2 * D
+        window = 2 * D
+        prefer_f_below = 2 * D
+    else:
+        cap = 2 * D
+        window = D + D // 2
+        prefer_f_below = 0                  # always backwards first
     done_f, done_b = {}, {}             # (stage, mb) -> finish time
     free_at = [0] * D
     lanes = [[] for _ in range(D)]
@@ -93,8 +109,11 @@ def generate_timeline(D, N, cost_f=1, cost_b=2):
                                 ready_f.append((0, mb, dr))
                         elif done_f.get((s - 1, mb), never) <= t:
                             ready_f.append((-s, mb, dr))
-            if ready_b:
-                mb, s, dr = min(ready_b)
+            if ready_b and not (ready_f and held < prefer_f_below):
+                if early_forward:       # lowest stage first, then lowest micro-batch
+                    mb, s, dr = min(ready_b, key=lambda c: (c[1], c[0]))
+                else:                   # lowest micro-batch first, then lowest stage
+                    mb, s, dr = min(ready_b)
                 started.add(("B", s, mb))
                 done_b[(s, mb)] = t + cost_b
                 free_at[dev] = t + cost_b
@@ -119,8 +138,8 @@ def serialise(lanes):
     return [sl.op for sl in slots]
 
 
-def generate(D, N):
-    return serialise(generate_timeline(D, N))
+def generate(D, N, early_forward=False):
+    return serialise(generate_timeline(D, N, early_forward=early_forward))
 
 
 def makespan(lanes):

@@ -31,6 +31,10 @@ struct Timed {
 // State of the list scheduler: finish times per (stage, mb), busy-until per device.
 struct ListScheduler {
     int D, N, n_stage, cost_f, cost_b;
+    // rule parameters: most chunk stashes per device, most micro-batches in flight, and the stash
+    // count below which a device prefers a ready forward to a ready backward (0: never)
+    int cap, window, prefer_f_below;
+    bool b_lowest_stage_first;               // else: lowest micro-batch first
     std::vector<int> f_done, b_done;        // finish time or INT_MAX while not finished
     std::vector<char> f_started, b_started;
     std::vector<int> busy_until, f_count;
@@ -38,8 +42,12 @@ struct ListScheduler {
     std::vector<int> admitted;
     std::vector<Timed> out;
 
-    ListScheduler(int D_, int N_, int cf, int cb)
+    ListScheduler(int D_, int N_, int cf, int cb, int variant)
         : D(D_), N(N_), n_stage(2 * D_), cost_f(cf), cost_b(cb),
+          cap(variant == BP_SCHED_V_EARLY_FWD ? (D_ > 2 ? 3 * D_ - 3 : 2 * D_) : 2 * D_),
+          window(variant == BP_SCHED_V_EARLY_FWD ? 2 * D_ : D_ + D_ / 2),
+          prefer_f_below(variant == BP_SCHED_V_EARLY_FWD ? 2 * D_ : 0),
+          b_lowest_stage_first(variant == BP_SCHED_V_EARLY_FWD),
           f_done((size_t)2 * D_ * N_, INT_MAX), b_done((size_t)2 * D_ * N_, INT_MAX),
           f_started((size_t)2 * D_ * N_, 0), b_started((size_t)2 * D_ * N_, 0),
           busy_until(D_, 0), f_count(D_, 0), b_ends(D_) {}
@@ -57,13 +65,15 @@ struct ListScheduler {
         return n;
     }
 
-    // Pick what device `dev` starts at time t, or nothing.  Backwards first (lowest micro-batch,
-    // then lowest stage); else the forward of the deepest stage (then lowest micro-batch).
+    // Pick what device `dev` starts at time t, or nothing.  Concatenated units: backwards first
+    // (lowest micro-batch, then lowest stage); else the forward of the deepest stage (then lowest
+    // micro-batch).  Early forwarding (Appendix B): the forward goes first while the device holds
+    // fewer than prefer_f_below stashes, and among backwards the lowest stage wins.
     bool pick(int dev, int t, bp_op* chosen) const {
-        const int cap = 2 * D, window = D + D / 2;
         bool have_b = false, have_f = false;
         int b_mb = 0, b_s = 0, f_mb = 0, f_s = 0;
-        const bool room = held(dev, t) < cap;
+        const int holding = held(dev, t);
+        const bool room = holding < cap;
         const bool may_admit = in_flight(t) < window;
         for (int mb = 0; mb < N; ++mb) {
             const int dir = direction_of(mb, D);
@@ -72,7 +82,9 @@ struct ListScheduler {
                 const size_t k = at(s, mb);
                 if (!b_started[k] && f_done[k] <= t &&
                     (s == n_stage - 1 || b_done[at(s + 1, mb)] <= t)) {
-                    if (!have_b || mb < b_mb || (mb == b_mb && s < b_s)) { have_b = true; b_mb = mb; b_s = s; }
+                    const bool better = b_lowest_stage_first ? (s < b_s || (s == b_s && mb < b_mb))
+                                                             : (mb < b_mb || (mb == b_mb && s < b_s));
+                    if (!have_b || better) { have_b = true; b_mb = mb; b_s = s; }
                 }
                 if (!f_started[k] && room) {
                     const bool ready = s == 0 ? may_admit : f_done[at(s - 1, mb)] <= t;
@@ -80,7 +92,7 @@ struct ListScheduler {
                 }
             }
         }
-        if (have_b) {
+        if (have_b && !(have_f && holding < prefer_f_below)) {
             *chosen = bp_op{1, (int8_t)direction_of(b_mb, D), (int16_t)dev, b_s, b_mb};
             return true;
         }
@@ -123,13 +135,14 @@ struct ListScheduler {
 }  // namespace
 
 static int schedule_generate(int D, int N, int variant, bp_op* out, int cap, int* n_out) {
-    if (variant != BP_SCHED_V_CONCAT) return fail(BP_EINVAL, "unknown schedule variant %d", variant);
+    if (variant != BP_SCHED_V_CONCAT && variant != BP_SCHED_V_EARLY_FWD)
+        return fail(BP_EINVAL, "unknown schedule variant %d", variant);
     if (D < 2 || D % 2) return fail(BP_EINVAL, "D = %d must be even and >= 2", D);
     if (N < D || N % D) return fail(BP_EINVAL, "N = %d must be a positive multiple of D = %d", N, D);
     if (D > 1024 || N > 65536) return fail(BP_EINVAL, "D or N too large");
     const long total = 4L * D * N;
     if (!out || !n_out || cap < total) return fail(BP_EINVAL, "output array too small (need %ld ops)", total);
-    ListScheduler ls(D, N, 1, 2);
+    ListScheduler ls(D, N, 1, 2, variant);
     if (!ls.run()) return fail(BP_EINVAL, "list scheduler made no progress for D = %d, N = %d", D, N);
     // one GPU runs the devices' ops one after another: order by (start time, device)
     std::stable_sort(ls.out.begin(), ls.out.end(), [](const Timed& a, const Timed& b) {

@@ -56,6 +56,19 @@ def test_v_schedule_iteration_bf16_D4_N8():
     print("worst grad err", worst)
 
 
+def test_early_forwarding_order_same_gradients_D4_N8():
+    """Appendix B: the early-forwarding order only moves forwards ahead of time; executed on the GPU
+    it must give the loss and gradients of the full-batch oracle, like the concatenated order."""
+    import paper_2410_19367_amd as bp
+    cfg = si.scaled(si.CONFIGS[4], name="sched_ef", layers=1, hidden=128, heads=2, seq=128)
+    order = bp.ops_to_tuples(bp.bp_schedule_generate(4, cfg.n_micro, variant=1))
+    assert order == [tuple(o) for o in so.generate(4, cfg.n_micro, early_forward=True)]
+    loss_ef, grads_ef, worst = _run_iteration(cfg, 4, order_tuples=order)
+    loss_cc, grads_cc, _ = _run_iteration(cfg, 4)
+    assert abs(loss_ef - loss_cc) <= 1e-3 * abs(loss_cc)
+    print("early forwarding worst grad err", worst)
+
+
 def test_v_schedule_iteration_bert_padded():
     cfg = si.scaled(si.CONFIGS[4], name="sched_bert", layers=1, hidden=128, heads=2, seq=96,
                     causal=False, len_lo=20, len_hi=96, n_chunks=4, n_micro=4, microbatch=2)

@@ -42,6 +42,20 @@ def test_generated_order_is_the_oracles(D, N):
     assert max(peak) <= 2 * D
 
 
+@pytest.mark.parametrize("D,N", [(2, 4), (4, 4), (4, 8), (4, 12), (4, 16), (6, 12), (8, 16)])
+def test_early_forwarding_order_is_the_oracles(D, N):
+    order = bp.bp_schedule_generate(D, N, variant=1)
+    assert bp.ops_to_tuples(order) == [tuple(o) for o in so.generate(D, N, early_forward=True)]
+    bp.bp_schedule_validate(order, D, N)
+
+
+def test_simulate_reproduces_the_early_forwarding_closed_forms_at_D4():
+    for N in (8, 12, 16):
+        order = bp.bp_schedule_generate(4, N, variant=1)
+        ms, idle, peak = bp.bp_schedule_simulate(order, 4, N)
+        assert (ms, idle, max(peak)) == (6 * N + 3, [3, 3, 3, 3], 9)
+
+
 def test_simulate_reproduces_the_closed_forms_at_D4():
     order = bp.bp_schedule_generate(4, 4)
     ms, idle, peak = bp.bp_schedule_simulate(order, 4, 4)

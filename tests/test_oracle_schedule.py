@@ -95,6 +95,42 @@ def test_concatenation_fills_tail_bubbles_D4():
     assert ms == 53
 
 
+def _golden_early_forward_rows():
+    import os
+    p = os.path.join(os.path.dirname(__file__), "golden", "paper_bitpipe_closed_forms.txt")
+    return [[float(v) for v in line.split()[1:]] for line in open(p) if line.startswith("EF")]
+
+
+@pytest.mark.parametrize("row", _golden_early_forward_rows())
+def test_early_forwarding_closed_forms_D4(row):
+    """Appendix B, Eq. 1-2 at D = 4 from the golden fixture: idle (D-2)/4 (t_f + t_b) per device
+    with t_f = 2, t_b = 4 chunk units, bubble ratio (D-2)/(4N+D-2), peak (3D-3)/2 M_a = 3D-3
+    chunk stashes; and the order is a valid, conflict-free BitPipe iteration."""
+    D, N, num, den, idle_df, peak_ma = row
+    D, N = int(D), int(N)
+    lanes = so.generate_timeline(D, N, early_forward=True)
+    assert so.conflicts(lanes) == 0
+    assert so.validate(so.serialise(lanes), D, N) is None
+    ms = so.makespan(lanes)
+    idle = so.idle_per_device(lanes)
+    assert all(i == int(idle_df * 2) == 3 for i in idle)
+    assert ms == 6 * N + 3                                  # ideal N (t_f + t_b) plus the bubbles
+    assert all(Fraction(i, ms) == Fraction(int(num), int(den)) for i in idle)
+    assert max(so.peak_stash(lanes)) == int(peak_ma * 2) == 3 * D - 3
+    # fewer bubbles than direct concatenation, whose closed form is 2 (3N + D - 2)
+    assert ms < 2 * (3 * N + D - 2) <= so.makespan(so.generate_timeline(D, N))
+
+
+@pytest.mark.parametrize("D,N", [(2, 4), (4, 4), (6, 12), (8, 16), (8, 32)])
+def test_early_forwarding_orders_are_valid_for_other_sizes(D, N):
+    """Beyond the pinned sizes the rule still has to give a complete, dependency-respecting,
+    conflict-free order within its stash cap (the closed forms are not claimed there)."""
+    lanes = so.generate_timeline(D, N, early_forward=True)
+    assert so.conflicts(lanes) == 0
+    assert so.validate(so.serialise(lanes), D, N) is None
+    assert max(so.peak_stash(lanes)) <= max(3 * D - 3, 2 * D if D == 2 else 0)
+
+
 def test_d2_has_no_bubbles():
     # (D-2)/(3N+D-2) = 0 at D = 2
     for N in (2, 4, 8):
