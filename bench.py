@@ -240,8 +240,9 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count() or 1
-        # bounded sample: one micro-batch through a one-layer chunk of the same shape
-        sample_layers = 1
+        # bounded sample (10-30 s of CPU work): one micro-batch through the whole chunk for the
+        # 2048-wide configs, through one layer for the wider ones
+        sample_layers = cfg.layers if cfg.hidden * cfg.T <= 2048 * 4096 else 1
         scfg = si.scaled(cfg, layers=sample_layers)
         orc = O.StageOracle(sample_layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, cfg.causal,
                             mlp=cfg.mlp, ln_eps=cfg.ln_eps)
@@ -260,9 +261,9 @@ def main():
             "unit": "TFLOP/s",
             "cores": int(cores),
             "kind": "oracle",
-            "sample": f"fp64 numpy oracle, 1 micro-batch fwd+bwd through 1 of the {cfg.layers} layers "
+            "sample": f"fp64 numpy oracle, 1 micro-batch fwd+bwd through {sample_layers} of the {cfg.layers} layers "
                       f"at full shape ({cdt:.1f} s)",
-            "tokens_per_s": round(cfg.T / (cdt * cfg.layers), 2),
+            "tokens_per_s": round(cfg.T * sample_layers / (cdt * cfg.layers), 2),
         }
 
     bp.bp_stage_destroy(st)
