@@ -183,6 +183,37 @@ int bp_schedule_simulate(const bp_op* order, int n_ops, int D, int N, int cost_f
 int bp_run_schedule(bp_stage_t* st, const bp_op* order, int n_ops, int D,
                     const void* inputs_dev, const void* targets_dev, float* loss_out);
 
+/* ---- other stage placements (Appendix A; the "w/o V" ablation of Section 4.4).
+ * v: chunks per device and pipeline, so a pipeline has v*D stages (the default V shape is v = 2;
+ * v = 1 is one chunk per device and direction).  looping = 0: the walk over the devices turns
+ * round at both ends (0..D-1, D-1..0, 0..D-1, ...), every turn being a local copy; looping = 1:
+ * the placement of the plain interleaved schedule, which restarts at device 0 after each lap and
+ * has no local copies.  A NULL layout means {2, 0}.  The *_ex calls below are the calls above for
+ * an arbitrary layout: stages run from 0 to v*D-1, an order holds 2*v*D*N ops, the stage object
+ * must hold v*D chunks.  Stash caps of the list scheduler scale with v (a stage-activation M_a is
+ * v chunk stashes).  The closed forms of the paper are pinned for {2, 0} only. */
+typedef struct bp_layout {
+    int v;
+    int looping;
+} bp_layout;
+
+int bp_schedule_vmap_ex(const bp_layout* layout, int dir, int stage, int D);
+int bp_schedule_generate_ex(const bp_layout* layout, int D, int N, int variant, bp_op* out, int cap,
+                            int* n_out);
+int bp_schedule_validate_ex(const bp_layout* layout, const bp_op* order, int n_ops, int D, int N);
+int bp_schedule_simulate_ex(const bp_layout* layout, const bp_op* order, int n_ops, int D, int N,
+                            int cost_f, int cost_b, int* makespan, int* idle, int* peak_stash);
+int bp_run_schedule_ex(bp_stage_t* st, const bp_layout* layout, const bp_op* order, int n_ops, int D,
+                       const void* inputs, const void* targets, float* loss_out);
+
+/* Pure CPU.  Messages of one iteration under a layout: every forward hands its output to the next
+ * stage and every backward its input gradient to the previous one.  *p2p counts the hand-overs
+ * between different devices (each a message of 2*B*S*H bytes, Appendix C), *local those that stay
+ * on a device.  For the zig-zag map: p2p = 2*N*v*(D-1), local = 2*N*(v-1); looping: p2p =
+ * 2*N*(v*D-1), local = 0.  Either output pointer may be NULL.  Errors as bp_schedule_validate. */
+int bp_schedule_hops(const bp_layout* layout, const bp_op* order, int n_ops, int D, int N,
+                     long* p2p, long* local);
+
 /* ---- per-kernel timing (HIP events recorded on the stage's stream around every launch) ---- */
 
 enum bp_kernel_id {

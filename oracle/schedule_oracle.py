@@ -38,14 +38,20 @@ Op = namedtuple("Op", "kind direction vdev stage mb")   # kind 'F'|'B'; directio
 Slot = namedtuple("Slot", "start end op")
 
 
-def vmap_down(stage, D):
-    """Device (0-based) of 0-based stage s in the down pipeline: 0..D-1 then D-1..0."""
-    return stage if stage < D else 2 * D - 1 - stage
+def vmap_down(stage, D, v=2, looping=False):
+    """Device (0-based) of 0-based stage s in the down pipeline of v*D stages.  Zig-zag (the V
+    shape for v = 2; Appendix A for more chunks per device): laps 0, 2, ... run 0..D-1 and laps
+    1, 3, ... run D-1..0, so consecutive laps meet on one device.  Looping (the interleaved
+    placement the paper's "w/o V" ablation falls back to): every lap runs 0..D-1."""
+    lap, pos = divmod(stage, D)
+    if not 0 <= lap < v:
+        raise ValueError("stage out of range")
+    return pos if looping or lap % 2 == 0 else D - 1 - pos
 
 
-def vmap(direction, stage, D):
+def vmap(direction, stage, D, v=2, looping=False):
     """Device of a stage in the down (0) or up (1, mirrored) pipeline."""
-    d = vmap_down(stage, D)
+    d = vmap_down(stage, D, v, looping)
     return d if direction == 0 else D - 1 - d
 
 
@@ -54,7 +60,7 @@ def direction_of(mb, D):
     return 0 if (mb % D) < D // 2 else 1
 
 
-def generate_timeline(D, N, cost_f=1, cost_b=2, early_forward=False):
+def generate_timeline(D, N, cost_f=1, cost_b=2, early_forward=False, v=2, looping=False):
     """List-schedule one iteration.  Returns per-device lists of Slot(start, end, op).
 
     Time advances in unit steps; at each step the devices are visited in index order and a free
@@ -64,16 +70,19 @@ def generate_timeline(D, N, cost_f=1, cost_b=2, early_forward=False):
     3D/2 admitted micro-batches still await their stage-0 backward: that lets the next basic
     unit's first forwards fill the tail bubbles of the previous one without flooding the
     stashes.  early_forward selects the Appendix-B rule described in the module header instead.
-    Raises RuntimeError if the greedy order stalls."""
+    v, looping: other stage placements (see vmap_down); a stage-activation M_a is then v chunk
+    stashes and the stash caps scale with it.  Raises RuntimeError if the greedy order stalls."""
     if D < 2 or D % 2 or N < D or N % D:
         raise ValueError("need even D >= 2 and N a positive multiple of D")
-    n_stage = 2 * D
+    if v < 1:
+        raise ValueError("need at least one chunk per device")
+    n_stage = v * D
     if early_forward:
-        cap = 3 * D - 3 if D > 2 else 2 * D
+        cap = -(-(3 * D - 3) * v // 2) if D > 2 else v * D      # (3D-3)/2 M_a, rounded up
         window = 2 * D
-        prefer_f_below = 2 * D
+        prefer_f_below = v * D
     else:
-        cap = 2 * D
+        cap = v * D                         # D M_a
         window = D + D // 2
         prefer_f_below = 0                  # always backwards first
     done_f, done_b = {}, {}             # (stage, mb) -> finish time
@@ -98,7 +107,7 @@ def generate_timeline(D, N, cost_f=1, cost_b=2, early_forward=False):
             for mb in range(N):
                 dr = direction_of(mb, D)
                 for s in range(n_stage):
-                    if vmap(dr, s, D) != dev:
+                    if vmap(dr, s, D, v, looping) != dev:
                         continue
                     if ("B", s, mb) not in started and done_f.get((s, mb), never) <= t:
                         if s == n_stage - 1 or done_b.get((s + 1, mb), never) <= t:
@@ -138,8 +147,8 @@ def serialise(lanes):
     return [sl.op for sl in slots]
 
 
-def generate(D, N, early_forward=False):
-    return serialise(generate_timeline(D, N, early_forward=early_forward))
+def generate(D, N, early_forward=False, v=2, looping=False):
+    return serialise(generate_timeline(D, N, early_forward=early_forward, v=v, looping=looping))
 
 
 def makespan(lanes):
@@ -181,19 +190,19 @@ def conflicts(lanes):
     return bad
 
 
-def validate(order, D, N):
+def validate(order, D, N, v=2, looping=False):
     """Check a serial order: every (stage, mb) has exactly one F and one B, each op's inputs
     precede it, the device matches the V map, a micro-batch keeps one direction.
     Returns None if valid, else a message naming the first violation."""
-    n_stage = 2 * D
+    n_stage = v * D
     seen_f, seen_b, mb_dir = set(), set(), {}
     for i, op in enumerate(order):
         if op.kind not in ("F", "B") or op.direction not in (0, 1):
             return f"op {i}: bad kind/direction"
         if not (0 <= op.stage < n_stage and 0 <= op.mb < N):
             return f"op {i}: stage/mb out of range"
-        if op.vdev != vmap(op.direction, op.stage, D):
-            return f"op {i}: device does not match the V map"
+        if op.vdev != vmap(op.direction, op.stage, D, v, looping):
+            return f"op {i}: device does not match the stage map"
         if mb_dir.setdefault(op.mb, op.direction) != op.direction:
             return f"op {i}: micro-batch changes direction"
         key = (op.stage, op.mb)
@@ -216,14 +225,28 @@ def validate(order, D, N):
     return None
 
 
-def cross_device_hops(order, D):
+def cross_device_hops(order, D, v=2, looping=False):
     """(cross-device hops, local copies) of the forward passes of one micro-batch's pipeline."""
     hops = local = 0
     mb0 = order[0].mb
     dr = [op.direction for op in order if op.mb == mb0][0]
-    for s in range(1, 2 * D):
-        if vmap(dr, s, D) == vmap(dr, s - 1, D):
+    for s in range(1, v * D):
+        if vmap(dr, s, D, v, looping) == vmap(dr, s - 1, D, v, looping):
             local += 1
         else:
             hops += 1
     return hops, local
+
+
+def messages(order, D, v=2, looping=False):
+    """(P2P messages, local copies) of a whole iteration: each forward hands its output to the
+    next stage, each backward its input gradient to the previous one (Appendix C counts both)."""
+    p2p = local = 0
+    for op in order:
+        to = op.stage + 1 if op.kind == "F" else op.stage - 1
+        if 0 <= to < v * D:
+            if vmap(op.direction, to, D, v, looping) == op.vdev:
+                local += 1
+            else:
+                p2p += 1
+    return p2p, local

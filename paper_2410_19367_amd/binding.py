@@ -26,7 +26,9 @@ EXPORTS = (
     "bp_stage_init", "bp_stage_init_ex", "bp_stage_destroy", "bp_stage_set_param",
     "bp_stage_get_grad", "bp_stage_zero_grad", "bp_stage_set_seqlens", "bp_stage_forward",
     "bp_stage_backward", "bp_stage_backward_dir", "bp_schedule_vmap", "bp_schedule_generate",
-    "bp_schedule_validate", "bp_schedule_simulate", "bp_run_schedule", "bp_prof_enable",
+    "bp_schedule_validate", "bp_schedule_simulate", "bp_run_schedule", "bp_schedule_vmap_ex",
+    "bp_schedule_generate_ex", "bp_schedule_validate_ex", "bp_schedule_simulate_ex", "bp_run_schedule_ex",
+    "bp_schedule_hops", "bp_prof_enable",
     "bp_prof_get", "bp_op_gemm", "bp_op_wgrad_group", "bp_op_layernorm_fwd", "bp_op_layernorm_bwd",
     "bp_op_bias_gelu_fwd", "bp_op_bias_gelu_bwd", "bp_op_colsum_workspace",
     "bp_op_attention_fwd", "bp_op_attention_bwd", "bp_last_error", "bp_version",
@@ -37,6 +39,10 @@ class bp_opts(C.Structure):
     _fields_ = [("n_chunks", C.c_int), ("mlp", C.c_int), ("dtype", C.c_int),
                 ("max_inflight", C.c_int), ("ln_eps", C.c_float), ("hip_stream", C.c_void_p),
                 ("wgrad_group", C.c_int)]
+
+
+class bp_layout(C.Structure):
+    _fields_ = [("v", C.c_int), ("looping", C.c_int)]
 
 
 class bp_op(C.Structure):
@@ -78,6 +84,14 @@ def lib():
         l.bp_schedule_simulate.argtypes = [C.POINTER(bp_op), ci, ci, ci, ci, ci, C.POINTER(ci),
                                            C.POINTER(ci), C.POINTER(ci)]
         l.bp_run_schedule.argtypes = [vp, C.POINTER(bp_op), ci, ci, vp, vp, C.POINTER(cf)]
+        lp = C.POINTER(bp_layout)
+        l.bp_schedule_vmap_ex.argtypes = [lp, ci, ci, ci]
+        l.bp_schedule_generate_ex.argtypes = [lp, ci, ci, ci, C.POINTER(bp_op), ci, C.POINTER(ci)]
+        l.bp_schedule_validate_ex.argtypes = [lp, C.POINTER(bp_op), ci, ci, ci]
+        l.bp_schedule_simulate_ex.argtypes = [lp, C.POINTER(bp_op), ci, ci, ci, ci, ci, C.POINTER(ci),
+                                              C.POINTER(ci), C.POINTER(ci)]
+        l.bp_run_schedule_ex.argtypes = [vp, lp, C.POINTER(bp_op), ci, ci, vp, vp, C.POINTER(cf)]
+        l.bp_schedule_hops.argtypes = [lp, C.POINTER(bp_op), ci, ci, ci, C.POINTER(C.c_long), C.POINTER(C.c_long)]
         l.bp_prof_enable.argtypes = [vp, ci]
         l.bp_prof_get.argtypes = [vp, ci, C.POINTER(C.c_double), C.POINTER(C.c_longlong),
                                   C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -220,6 +234,44 @@ def bp_schedule_simulate(order, D, N, cost_f=1, cost_b=2):
 def bp_run_schedule(st, order, D, inputs, targets) -> float:
     loss = C.c_float(0)
     _check(lib().bp_run_schedule(st, order, len(order), D, _ptr(inputs), _ptr(targets), C.byref(loss)))
+    return loss.value
+
+
+def bp_schedule_vmap_ex(layout, direction, stage, D):
+    return lib().bp_schedule_vmap_ex(C.byref(layout), direction, stage, D)
+
+
+def bp_schedule_generate_ex(layout, D, N, variant=0):
+    cap = 2 * max(layout.v, 0) * max(D, 0) * max(N, 0) + 1
+    arr = (bp_op * cap)()
+    n = C.c_int(0)
+    _check(lib().bp_schedule_generate_ex(C.byref(layout), D, N, variant, arr, cap, C.byref(n)))
+    return (bp_op * n.value)(*arr[:n.value])
+
+
+def bp_schedule_validate_ex(layout, order, D, N):
+    return _check(lib().bp_schedule_validate_ex(C.byref(layout), order, len(order), D, N))
+
+
+def bp_schedule_simulate_ex(layout, order, D, N, cost_f=1, cost_b=2):
+    ms = C.c_int(0)
+    idle = (C.c_int * D)()
+    peak = (C.c_int * D)()
+    _check(lib().bp_schedule_simulate_ex(C.byref(layout), order, len(order), D, N, cost_f, cost_b,
+                                         C.byref(ms), idle, peak))
+    return ms.value, list(idle), list(peak)
+
+
+def bp_schedule_hops(layout, order, D, N):
+    p2p, local = C.c_long(0), C.c_long(0)
+    _check(lib().bp_schedule_hops(C.byref(layout), order, len(order), D, N, C.byref(p2p), C.byref(local)))
+    return p2p.value, local.value
+
+
+def bp_run_schedule_ex(st, layout, order, D, inputs, targets) -> float:
+    loss = C.c_float(0)
+    _check(lib().bp_run_schedule_ex(st, C.byref(layout), order, len(order), D, _ptr(inputs), _ptr(targets),
+                                    C.byref(loss)))
     return loss.value
 
 

@@ -17,6 +17,12 @@ const char* last_error();
 
 struct Stage;
 
+// Stage placement of a pipeline: v chunks per device, zig-zag (the V shape for v = 2) or looping.
+struct Layout {
+    int v = 2;
+    bool looping = false;
+};
+
 // Optional event timing of every launch, grouped by kernel class.
 struct Prof {
     struct Pending { int kid; hipEvent_t start, stop; };
@@ -148,12 +154,13 @@ struct Stage {
     int sync_all();
     int forward(int chunk, int mb, const void* act_in, void* act_out);
     int backward(int chunk, int mb, const void* grad_out, void* grad_in, int dir);
-    int run_schedule(const bp_op* order, int n_ops, int D, const void* inputs, const void* targets,
-                     float* loss_out);
+    int run_schedule(const Layout& L, const bp_op* order, int n_ops, int D, const void* inputs,
+                     const void* targets, float* loss_out);
 };
 
 // pure CPU schedule logic
 int schedule_vmap(int dir, int stage, int D);
-int schedule_validate(const bp_op* order, int n_ops, int D, int N);
+int schedule_vmap(const Layout& L, int dir, int stage, int D);
+int schedule_validate(const Layout& L, const bp_op* order, int n_ops, int D, int N);
 
 }  // namespace bp

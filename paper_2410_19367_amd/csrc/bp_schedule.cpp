@@ -10,12 +10,17 @@
 namespace bp {
 
 // Section 3.2 / 3.3: the down pipeline places stages 0..D-1 on devices 0..D-1 and stages
-// D..2D-1 on devices D-1..0; the up pipeline is its mirror image.
-int schedule_vmap(int dir, int stage, int D) {
-    if (D <= 0 || stage < 0 || stage >= 2 * D || (dir != 0 && dir != 1)) return -1;
-    const int down = stage < D ? stage : 2 * D - 1 - stage;
+// D..2D-1 on devices D-1..0; the up pipeline is its mirror image.  With v chunks per device
+// (Appendix A) the walk keeps turning round at both ends (0..D-1, D-1..0, 0..D-1, ...), so every
+// turn is a local copy; the looping placement of the plain interleaved schedule (the paper's
+// "w/o V" ablation) restarts at device 0 instead and has no local copies.
+int schedule_vmap(const Layout& L, int dir, int stage, int D) {
+    if (D <= 0 || L.v < 1 || stage < 0 || stage >= L.v * D || (dir != 0 && dir != 1)) return -1;
+    const int lap = stage / D, pos = stage % D;
+    const int down = (L.looping || lap % 2 == 0) ? pos : D - 1 - pos;
     return dir == 0 ? down : D - 1 - down;
 }
+int schedule_vmap(int dir, int stage, int D) { return schedule_vmap(Layout{}, dir, stage, D); }
 
 // Within each group of D consecutive micro-batches the first half travels down, the second up
 // (each pipeline schedules N/2 micro-batches, Section 3.3).
@@ -30,6 +35,7 @@ struct Timed {
 
 // State of the list scheduler: finish times per (stage, mb), busy-until per device.
 struct ListScheduler {
+    Layout L;
     int D, N, n_stage, cost_f, cost_b;
     // rule parameters: most chunk stashes per device, most micro-batches in flight, and the stash
     // count below which a device prefers a ready forward to a ready backward (0: never)
@@ -42,14 +48,15 @@ struct ListScheduler {
     std::vector<int> admitted;
     std::vector<Timed> out;
 
-    ListScheduler(int D_, int N_, int cf, int cb, int variant)
-        : D(D_), N(N_), n_stage(2 * D_), cost_f(cf), cost_b(cb),
-          cap(variant == BP_SCHED_V_EARLY_FWD ? (D_ > 2 ? 3 * D_ - 3 : 2 * D_) : 2 * D_),
+    // A stage-activation M_a is v chunk stashes; the caps below are D M_a and (3D-3)/2 M_a.
+    ListScheduler(const Layout& L_, int D_, int N_, int cf, int cb, int variant)
+        : L(L_), D(D_), N(N_), n_stage(L_.v * D_), cost_f(cf), cost_b(cb),
+          cap(variant == BP_SCHED_V_EARLY_FWD ? (D_ > 2 ? ((3 * D_ - 3) * L_.v + 1) / 2 : L_.v * D_) : L_.v * D_),
           window(variant == BP_SCHED_V_EARLY_FWD ? 2 * D_ : D_ + D_ / 2),
-          prefer_f_below(variant == BP_SCHED_V_EARLY_FWD ? 2 * D_ : 0),
+          prefer_f_below(variant == BP_SCHED_V_EARLY_FWD ? L_.v * D_ : 0),
           b_lowest_stage_first(variant == BP_SCHED_V_EARLY_FWD),
-          f_done((size_t)2 * D_ * N_, INT_MAX), b_done((size_t)2 * D_ * N_, INT_MAX),
-          f_started((size_t)2 * D_ * N_, 0), b_started((size_t)2 * D_ * N_, 0),
+          f_done((size_t)L_.v * D_ * N_, INT_MAX), b_done((size_t)L_.v * D_ * N_, INT_MAX),
+          f_started((size_t)L_.v * D_ * N_, 0), b_started((size_t)L_.v * D_ * N_, 0),
           busy_until(D_, 0), f_count(D_, 0), b_ends(D_) {}
 
     size_t at(int s, int mb) const { return (size_t)mb * n_stage + s; }
@@ -78,7 +85,7 @@ struct ListScheduler {
         for (int mb = 0; mb < N; ++mb) {
             const int dir = direction_of(mb, D);
             for (int s = 0; s < n_stage; ++s) {
-                if (schedule_vmap(dir, s, D) != dev) continue;
+                if (schedule_vmap(L, dir, s, D) != dev) continue;
                 const size_t k = at(s, mb);
                 if (!b_started[k] && f_done[k] <= t &&
                     (s == n_stage - 1 || b_done[at(s + 1, mb)] <= t)) {
@@ -134,15 +141,21 @@ struct ListScheduler {
 
 }  // namespace
 
-static int schedule_generate(int D, int N, int variant, bp_op* out, int cap, int* n_out) {
+static int check_layout(const Layout& L) {
+    if (L.v < 1 || L.v > 64) return fail(BP_EINVAL, "v = %d chunks per device is outside 1..64", L.v);
+    return BP_OK;
+}
+
+static int schedule_generate(const Layout& L, int D, int N, int variant, bp_op* out, int cap, int* n_out) {
+    if (check_layout(L)) return BP_EINVAL;
     if (variant != BP_SCHED_V_CONCAT && variant != BP_SCHED_V_EARLY_FWD)
         return fail(BP_EINVAL, "unknown schedule variant %d", variant);
     if (D < 2 || D % 2) return fail(BP_EINVAL, "D = %d must be even and >= 2", D);
     if (N < D || N % D) return fail(BP_EINVAL, "N = %d must be a positive multiple of D = %d", N, D);
     if (D > 1024 || N > 65536) return fail(BP_EINVAL, "D or N too large");
-    const long total = 4L * D * N;
+    const long total = 2L * L.v * D * N;
     if (!out || !n_out || cap < total) return fail(BP_EINVAL, "output array too small (need %ld ops)", total);
-    ListScheduler ls(D, N, 1, 2, variant);
+    ListScheduler ls(L, D, N, 1, 2, variant);
     if (!ls.run()) return fail(BP_EINVAL, "list scheduler made no progress for D = %d, N = %d", D, N);
     // one GPU runs the devices' ops one after another: order by (start time, device)
     std::stable_sort(ls.out.begin(), ls.out.end(), [](const Timed& a, const Timed& b) {
@@ -153,11 +166,12 @@ static int schedule_generate(int D, int N, int variant, bp_op* out, int cap, int
     return BP_OK;
 }
 
-int schedule_validate(const bp_op* order, int n_ops, int D, int N) {
+int schedule_validate(const Layout& L, const bp_op* order, int n_ops, int D, int N) {
     if (!order) return fail(BP_EINVAL, "order is null");
+    if (check_layout(L)) return BP_EINVAL;
     if (D < 2 || D % 2) return fail(BP_EINVAL, "D = %d must be even and >= 2", D);
     if (N < 1) return fail(BP_EINVAL, "N = %d must be positive", N);
-    const int n_stage = 2 * D;
+    const int n_stage = L.v * D;
     if ((long)n_ops != 2L * n_stage * N)
         return fail(BP_EDEP, "order has %d ops, an iteration needs %ld", n_ops, 2L * n_stage * N);
     std::vector<char> f_seen((size_t)n_stage * N, 0), b_seen((size_t)n_stage * N, 0);
@@ -168,8 +182,8 @@ int schedule_validate(const bp_op* order, int n_ops, int D, int N) {
             return fail(BP_EDEP, "op %d: bad kind or direction", i);
         if (o.stage < 0 || o.stage >= n_stage || o.mb < 0 || o.mb >= N)
             return fail(BP_EDEP, "op %d: stage %d or micro-batch %d out of range", i, o.stage, o.mb);
-        if (o.vdev != schedule_vmap(o.dir, o.stage, D))
-            return fail(BP_EDEP, "op %d: device %d does not match the V map", i, o.vdev);
+        if (o.vdev != schedule_vmap(L, o.dir, o.stage, D))
+            return fail(BP_EDEP, "op %d: device %d does not match the stage map", i, o.vdev);
         if (mb_dir[o.mb] < 0) mb_dir[o.mb] = o.dir;
         else if (mb_dir[o.mb] != o.dir) return fail(BP_EDEP, "op %d: micro-batch %d changes direction", i, o.mb);
         const size_t k = (size_t)o.mb * n_stage + o.stage;
@@ -189,12 +203,12 @@ int schedule_validate(const bp_op* order, int n_ops, int D, int N) {
     return BP_OK;   // n_ops == 2 * n_stage * N and no duplicates => every op is present
 }
 
-static int schedule_simulate(const bp_op* order, int n_ops, int D, int N, int cost_f, int cost_b,
+static int schedule_simulate(const Layout& L, const bp_op* order, int n_ops, int D, int N, int cost_f, int cost_b,
                              int* makespan, int* idle, int* peak_stash) {
-    int rc = schedule_validate(order, n_ops, D, N);
+    int rc = schedule_validate(L, order, n_ops, D, N);
     if (rc) return rc;
     if (cost_f <= 0 || cost_b <= 0) return fail(BP_EINVAL, "costs must be positive");
-    const int n_stage = 2 * D;
+    const int n_stage = L.v * D;
     std::vector<int> f_done((size_t)n_stage * N, 0), b_done((size_t)n_stage * N, 0), busy(D, 0), work(D, 0);
     std::vector<std::vector<std::pair<int, int>>> events(D);   // (time, +1 at F start / -1 at B end)
     int ms = 0;
@@ -226,6 +240,25 @@ static int schedule_simulate(const bp_op* order, int n_ops, int D, int N, int co
     return BP_OK;
 }
 
+// Messages of one iteration: every forward hands its output to the next stage and every backward
+// its input gradient to the previous one; between different devices that is a P2P message of
+// 2 B S H bytes (Appendix C), on the same device (the turns of the zig-zag map) a local copy.
+static int schedule_hops(const Layout& L, const bp_op* order, int n_ops, int D, int N, long* p2p, long* local) {
+    int rc = schedule_validate(L, order, n_ops, D, N);
+    if (rc) return rc;
+    const int n_stage = L.v * D;
+    long hop = 0, loc = 0;
+    for (int i = 0; i < n_ops; ++i) {
+        const bp_op& o = order[i];
+        const int to = o.kind == 0 ? o.stage + 1 : o.stage - 1;
+        if (to < 0 || to >= n_stage) continue;
+        (schedule_vmap(L, o.dir, to, D) == o.vdev ? loc : hop) += 1;
+    }
+    if (p2p) *p2p = hop;
+    if (local) *local = loc;
+    return BP_OK;
+}
+
 // ------------------------------------------------------------------ executor
 
 int Stage::live_slots() const {
@@ -234,14 +267,17 @@ int Stage::live_slots() const {
     return n;
 }
 
-int Stage::run_schedule(const bp_op* order, int n_ops, int D, const void* inputs, const void* targets,
-                        float* loss_out) {
+int Stage::run_schedule(const Layout& L, const bp_op* order, int n_ops, int D, const void* inputs,
+                        const void* targets, float* loss_out) {
     if (!order || !inputs || !targets) return fail(BP_EINVAL, "null argument");
+    if (check_layout(L)) return BP_EINVAL;
     if (D < 2 || D % 2) return fail(BP_EINVAL, "D = %d must be even and >= 2", D);
-    if (n_chunks != 2 * D) return fail(BP_EINVAL, "stage object holds %d chunks, the order needs 2*D = %d", n_chunks, 2 * D);
-    if (n_ops <= 0 || n_ops % (4 * D)) return fail(BP_EDEP, "order has %d ops, not a multiple of 4*D", n_ops);
-    const int N = n_ops / (4 * D);
-    int rc = schedule_validate(order, n_ops, D, N);
+    const int n_stage = L.v * D;
+    if (n_chunks != n_stage)
+        return fail(BP_EINVAL, "stage object holds %d chunks, the order needs v*D = %d", n_chunks, n_stage);
+    if (n_ops <= 0 || n_ops % (2 * n_stage)) return fail(BP_EDEP, "order has %d ops, not a multiple of 2*v*D", n_ops);
+    const int N = n_ops / (2 * n_stage);
+    int rc = schedule_validate(L, order, n_ops, D, N);
     if (rc) return rc;
     if (live_slots()) return fail(BP_ESTATE, "stashes are live at the start of an iteration");
 
@@ -259,10 +295,10 @@ int Stage::run_schedule(const bp_op* order, int n_ops, int D, const void* inputs
         sched_n = N;
     }
     // an order may keep every (stage, mb) stashed at once; slots get memory only when used
-    if (slot_capacity < 2 * D * N) slot_capacity = 2 * D * N;
+    if (slot_capacity < n_stage * N) slot_capacity = n_stage * N;
 
     if ((rc = zero_grad())) return rc;
-    const int last = 2 * D - 1;
+    const int last = n_stage - 1;
     const float scale = 1.f / ((float)N * (float)B * (float)S);
     for (int i = 0; i < n_ops; ++i) {
         const bp_op& o = order[i];
@@ -303,25 +339,53 @@ int Stage::run_schedule(const bp_op* order, int n_ops, int D, const void* inputs
 
 extern "C" {
 
+static bp::Layout layout_of(const bp_layout* l) {
+    bp::Layout L;
+    if (l) { L.v = l->v; L.looping = l->looping != 0; }
+    return L;
+}
+
 int bp_schedule_vmap(int dir, int stage, int D) { return bp::schedule_vmap(dir, stage, D); }
+int bp_schedule_vmap_ex(const bp_layout* l, int dir, int stage, int D) {
+    return bp::schedule_vmap(layout_of(l), dir, stage, D);
+}
 
 int bp_schedule_generate(int D, int N, int variant, bp_op* out, int cap, int* n_out) {
-    return bp::schedule_generate(D, N, variant, out, cap, n_out);
+    return bp::schedule_generate(bp::Layout{}, D, N, variant, out, cap, n_out);
+}
+int bp_schedule_generate_ex(const bp_layout* l, int D, int N, int variant, bp_op* out, int cap, int* n_out) {
+    return bp::schedule_generate(layout_of(l), D, N, variant, out, cap, n_out);
 }
 
 int bp_schedule_validate(const bp_op* order, int n_ops, int D, int N) {
-    return bp::schedule_validate(order, n_ops, D, N);
+    return bp::schedule_validate(bp::Layout{}, order, n_ops, D, N);
+}
+int bp_schedule_validate_ex(const bp_layout* l, const bp_op* order, int n_ops, int D, int N) {
+    return bp::schedule_validate(layout_of(l), order, n_ops, D, N);
 }
 
 int bp_schedule_simulate(const bp_op* order, int n_ops, int D, int N, int cost_f, int cost_b,
                          int* makespan, int* idle, int* peak_stash) {
-    return bp::schedule_simulate(order, n_ops, D, N, cost_f, cost_b, makespan, idle, peak_stash);
+    return bp::schedule_simulate(bp::Layout{}, order, n_ops, D, N, cost_f, cost_b, makespan, idle, peak_stash);
+}
+int bp_schedule_simulate_ex(const bp_layout* l, const bp_op* order, int n_ops, int D, int N, int cost_f,
+                            int cost_b, int* makespan, int* idle, int* peak_stash) {
+    return bp::schedule_simulate(layout_of(l), order, n_ops, D, N, cost_f, cost_b, makespan, idle, peak_stash);
+}
+
+int bp_schedule_hops(const bp_layout* l, const bp_op* order, int n_ops, int D, int N, long* p2p, long* local) {
+    return bp::schedule_hops(layout_of(l), order, n_ops, D, N, p2p, local);
 }
 
 int bp_run_schedule(bp_stage_t* st, const bp_op* order, int n_ops, int D, const void* inputs,
                     const void* targets, float* loss_out) {
     if (!st) return bp::fail(BP_EINVAL, "stage handle is null");
-    return ((bp::Stage*)st)->run_schedule(order, n_ops, D, inputs, targets, loss_out);
+    return ((bp::Stage*)st)->run_schedule(bp::Layout{}, order, n_ops, D, inputs, targets, loss_out);
+}
+int bp_run_schedule_ex(bp_stage_t* st, const bp_layout* l, const bp_op* order, int n_ops, int D,
+                       const void* inputs, const void* targets, float* loss_out) {
+    if (!st) return bp::fail(BP_EINVAL, "stage handle is null");
+    return ((bp::Stage*)st)->run_schedule(layout_of(l), order, n_ops, D, inputs, targets, loss_out);
 }
 
 }  // extern "C"

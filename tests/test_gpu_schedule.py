@@ -12,7 +12,7 @@ from tests import harness as hz
 pytestmark = pytest.mark.gpu
 
 
-def _run_iteration(cfg, D, order_tuples=None, seed=0, expect_tol=None):
+def _run_iteration(cfg, D, order_tuples=None, seed=0, expect_tol=None, layout=None):
     import paper_2410_19367_amd as bp
     N = cfg.n_micro
     params = si.make_params(cfg, seed, ln_jitter=0.1)
@@ -28,8 +28,14 @@ def _run_iteration(cfg, D, order_tuples=None, seed=0, expect_tol=None):
         if lens is not None:
             for m in range(N):
                 bp.bp_stage_set_seqlens(g.h, m, lens[m])
-        order = bp.bp_schedule_generate(D, N) if order_tuples is None else bp.ops_from_tuples(order_tuples)
-        loss = bp.bp_run_schedule(g.h, order, D, hz.to_dev(inputs, cfg.dtype), hz.to_dev(targets, cfg.dtype))
+        if layout is None:
+            order = bp.bp_schedule_generate(D, N) if order_tuples is None else bp.ops_from_tuples(order_tuples)
+            loss = bp.bp_run_schedule(g.h, order, D, hz.to_dev(inputs, cfg.dtype), hz.to_dev(targets, cfg.dtype))
+        else:
+            lay = bp.bp_layout(*layout)
+            order = bp.bp_schedule_generate_ex(lay, D, N)
+            loss = bp.bp_run_schedule_ex(g.h, lay, order, D, hz.to_dev(inputs, cfg.dtype),
+                                         hz.to_dev(targets, cfg.dtype))
         tol = expect_tol or hz.TOL[cfg.dtype]
         assert abs(loss - loss_ref) <= tol * abs(loss_ref), (loss, loss_ref)
         errs = {}
@@ -67,6 +73,30 @@ def test_early_forwarding_order_same_gradients_D4_N8():
     loss_cc, grads_cc, _ = _run_iteration(cfg, 4)
     assert abs(loss_ef - loss_cc) <= 1e-3 * abs(loss_cc)
     print("early forwarding worst grad err", worst)
+
+
+@pytest.mark.parametrize("D,v,looping", [(2, 4, 0), (4, 2, 1), (2, 3, 1), (4, 1, 0)])
+def test_other_layouts_same_gradients(D, v, looping):
+    """Appendix A (more chunks per device) and the looping placement of the "w/o V" ablation run
+    through the same executor: v*D stages, loss and gradients of the full-batch oracle."""
+    cfg = si.scaled(si.CONFIGS[4], name=f"sched_v{v}_l{looping}", layers=1, hidden=128, heads=2, seq=64,
+                    n_chunks=v * D, n_micro=2 * D)
+    loss, grads, worst = _run_iteration(cfg, D, layout=(v, looping))
+    print("layout", (D, v, looping), "worst grad err", worst)
+
+
+def test_order_of_one_layout_is_rejected_under_another():
+    import paper_2410_19367_amd as bp
+    cfg = si.scaled(si.CONFIGS[0], name="sched_lay_bad", layers=1, n_chunks=8, n_micro=4, microbatch=1)
+    with hz.GpuStage(cfg) as g:
+        order = bp.bp_schedule_generate_ex(bp.bp_layout(2, 1), 4, 4)      # looping order
+        x = hz.to_dev(np.zeros((4, cfg.microbatch, cfg.seq, cfg.hidden)), cfg.dtype)
+        with pytest.raises(bp.BitPipeError) as e:
+            bp.bp_run_schedule(g.h, order, 4, x, x)                        # executed as the V shape
+        assert e.value.code == bp.BP_EDEP
+        with pytest.raises(bp.BitPipeError) as e:                          # 8 chunks are not v*D = 16
+            bp.bp_run_schedule_ex(g.h, bp.bp_layout(4, 0), bp.bp_schedule_generate_ex(bp.bp_layout(4, 0), 4, 4), 4, x, x)
+        assert e.value.code == bp.BP_EINVAL
 
 
 def test_v_schedule_iteration_bert_padded():

@@ -49,6 +49,39 @@ def test_early_forwarding_order_is_the_oracles(D, N):
     bp.bp_schedule_validate(order, D, N)
 
 
+@pytest.mark.parametrize("D,N,v,looping,variant", [(4, 4, 4, 0, 0), (4, 8, 4, 0, 0), (4, 8, 2, 1, 0), (2, 4, 3, 0, 0),
+                                                   (4, 4, 1, 0, 0), (6, 6, 4, 1, 0), (4, 8, 3, 1, 0), (4, 8, 4, 0, 1),
+                                                   (4, 8, 2, 0, 1), (4, 4, 2, 0, 0)])
+def test_other_layouts_agree_with_oracle(D, N, v, looping, variant):
+    lay = bp.bp_layout(v, looping)
+    for dr in (0, 1):
+        for s in range(v * D):
+            assert bp.bp_schedule_vmap_ex(lay, dr, s, D) == so.vmap(dr, s, D, v, bool(looping))
+    assert bp.bp_schedule_vmap_ex(lay, 0, v * D, D) == -1
+    order = bp.bp_schedule_generate_ex(lay, D, N, variant)
+    ref = so.generate(D, N, early_forward=bool(variant), v=v, looping=bool(looping))
+    assert bp.ops_to_tuples(order) == [tuple(o) for o in ref]
+    bp.bp_schedule_validate_ex(lay, order, D, N)
+    lanes = so.generate_timeline(D, N, early_forward=bool(variant), v=v, looping=bool(looping))
+    ms, idle, peak = bp.bp_schedule_simulate_ex(lay, order, D, N)
+    assert ms <= so.makespan(lanes)
+    assert bp.bp_schedule_hops(lay, order, D, N) == so.messages(ref, D, v, bool(looping))
+    if v > 1:       # the same ops do not fit the other map
+        with pytest.raises(bp.BitPipeError) as e:
+            bp.bp_schedule_validate_ex(bp.bp_layout(v, 1 - looping), order, D, N)
+        assert e.value.code == bp.BP_EDEP
+
+
+def test_layout_argument_checks():
+    with pytest.raises(bp.BitPipeError) as e:
+        bp.bp_schedule_generate_ex(bp.bp_layout(0, 0), 4, 4)
+    assert e.value.code == bp.BP_EINVAL
+    # the plain calls are the layout {2, 0}
+    a = bp.ops_to_tuples(bp.bp_schedule_generate(4, 8))
+    b = bp.ops_to_tuples(bp.bp_schedule_generate_ex(bp.bp_layout(2, 0), 4, 8))
+    assert a == b
+
+
 def test_simulate_reproduces_the_early_forwarding_closed_forms_at_D4():
     for N in (8, 12, 16):
         order = bp.bp_schedule_generate(4, N, variant=1)

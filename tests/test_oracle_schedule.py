@@ -283,3 +283,55 @@ def test_closed_forms_are_lower_bounds_at_D4(N, closed_form):
     assert not _fits_in(4, N, closed_form - 1)
     gen = so.generate_timeline(4, N, early_forward=N > 4)
     assert so.makespan(gen) == closed_form
+
+
+# ---- other stage placements: v chunks per device (Appendix A) and the looping map ("w/o V")
+
+def test_zigzag_and_looping_maps():
+    # v = 4 on D = 3 devices, down pipeline: 0 1 2 | 2 1 0 | 0 1 2 | 2 1 0; looping: 0 1 2 four times
+    assert [so.vmap(0, s, 3, v=4) for s in range(12)] == [0, 1, 2, 2, 1, 0, 0, 1, 2, 2, 1, 0]
+    assert [so.vmap(0, s, 3, v=4, looping=True) for s in range(12)] == [0, 1, 2] * 4
+    assert [so.vmap(1, s, 3, v=2, looping=True) for s in range(6)] == [2, 1, 0, 2, 1, 0]
+    # the default arguments are the V shape of Section 3.2
+    assert all(so.vmap(d, s, 4) == so.vmap(d, s, 4, v=2, looping=False) for d in (0, 1) for s in range(8))
+    with pytest.raises(ValueError):
+        so.vmap(0, 8, 4, v=2)
+
+
+@pytest.mark.parametrize("D,N,v,looping", [(4, 4, 4, False), (4, 8, 4, False), (4, 8, 2, True), (2, 4, 3, False),
+                                           (4, 4, 1, False), (6, 6, 4, True), (4, 8, 3, True)])
+def test_other_placements_give_valid_conflict_free_orders(D, N, v, looping):
+    lanes = so.generate_timeline(D, N, v=v, looping=looping)
+    order = so.serialise(lanes)
+    assert so.conflicts(lanes) == 0
+    assert so.validate(order, D, N, v, looping) is None
+    assert len(order) == 2 * v * D * N
+    assert max(so.peak_stash(lanes)) <= v * D              # D stage-activations of v chunk stashes
+    # an order built for one map is rejected under the other (unless the maps coincide: v = 1)
+    if v > 1:
+        assert so.validate(order, D, N, v, not looping) is not None
+
+
+@pytest.mark.parametrize("v", [1, 2, 4])
+def test_bubble_time_shrinks_in_proportion_to_the_chunk_size(v):
+    """Appendix A: with v chunks per device a chunk's forward and backward take 1/v of the time and
+    the bubble is proportional to that time.  In slots (one chunk forward = 1) the basic unit at
+    D = 4 therefore idles the same 4 slots per device for every v, i.e. 4 * (2/v) in units of the
+    v = 2 chunk, while the work per device grows to 3 N v slots."""
+    lanes = so.generate_timeline(4, 4, v=v)
+    assert so.idle_per_device(lanes) == [4, 4, 4, 4]
+    assert so.makespan(lanes) == 3 * 4 * v + 4
+
+
+@pytest.mark.parametrize("D,N,v", [(4, 4, 2), (4, 8, 2), (4, 4, 4), (6, 6, 3), (2, 2, 2)])
+def test_message_counts_of_the_two_maps(D, N, v):
+    """Section 3.2 and Appendix A/C: the zig-zag map turns every lap boundary into a local copy, so an
+    iteration sends 2 N v (D-1) messages and makes 2 N (v-1) local copies; the looping map sends
+    all 2 N (vD-1) hand-overs between devices; going from v to 2v doubles the messages."""
+    z = so.generate(D, N, v=v)
+    lo = so.generate(D, N, v=v, looping=True)
+    assert so.messages(z, D, v) == (2 * N * v * (D - 1), 2 * N * (v - 1))
+    assert so.messages(lo, D, v, looping=True) == (2 * N * (v * D - 1), 0)
+    z2 = so.generate(D, N, v=2 * v)
+    assert so.messages(z2, D, 2 * v)[0] == 2 * so.messages(z, D, v)[0]
+    assert so.cross_device_hops(z, D, v) == (v * (D - 1), v - 1)
