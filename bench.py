@@ -102,6 +102,9 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="index into synth_inputs.CONFIGS (1..3: baseline stage configs; 4: whole V-schedule iteration; 5, 6: stages of the paper's BERT-64 and GPT-96 at their own shapes)")
     ap.add_argument("--order", choices=["concat", "early"], default="concat",
                     help="config 4 only: concatenated basic units or early forwarding")
+    ap.add_argument("--stash-recompute", action="store_true",
+                    help="stage configs: keep 10 instead of 16 [T,H] tensors per layer in the stash and "
+                         "recompute the LayerNorm / GELU outputs for the weight gradients")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for FETCH_SIZE / WRITE_SIZE counters)")
@@ -143,7 +146,7 @@ def main():
 
     st = bp.bp_stage_init_ex(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, cfg.causal,
                              n_chunks=1, mlp=cfg.mlp, dtype=bp.BP_BF16 if cfg.dtype == "bf16" else bp.BP_F32,
-                             max_inflight=2, ln_eps=cfg.ln_eps)
+                             max_inflight=2, ln_eps=cfg.ln_eps, stash_recompute=int(args.stash_recompute))
     params = si.make_params(cfg)
     for l in range(cfg.layers):
         for name, tid in bp.TENSOR_IDS.items():
@@ -218,6 +221,7 @@ def main():
                    "micro_batches_per_step": cfg.n_micro},
         "tokens_per_s": round(tokens_step * args.steps / dt, 1),
         "ms_per_microbatch": round(ms_per_step / cfg.n_micro, 4),
+        "stash_bytes_per_microbatch": bp.bp_stage_stash_bytes(st),
         "mfma_util": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "roofline": {
             "kernel": "bf16 MFMA GEMM (forward, dgrad, wgrad of the four linear layers)",

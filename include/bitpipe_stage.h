@@ -74,6 +74,11 @@ typedef struct bp_opts {
                            group keeps the stashes of its waiting micro-batches (beyond
                            max_inflight) plus their output gradients until it is complete or
                            until bp_stage_get_grad / bp_run_schedule's merge flushes it.      */
+    int stash_recompute;/* 0: the stash keeps everything the backward reads, 16*T*H elements per
+                           layer (x, LN1 out, qkv, ctx, y, LN2 out, u, GELU out); 1: the two
+                           LayerNorm outputs and the GELU output are not kept (10*T*H per layer)
+                           and are recomputed from x, y, u right before the weight-gradient GEMMs
+                           that read them: the activation-memory axis of Table 2               */
 } bp_opts;
 
 /* Create a stage object holding one chunk of `layers` pre-LN transformer layers in bf16 with
@@ -89,6 +94,10 @@ int bp_stage_init(bp_stage_t** out, int layers, int hidden, int heads, int seq,
  * opts may be NULL (defaults). */
 int bp_stage_init_ex(bp_stage_t** out, int layers, int hidden, int heads, int seq,
                      int microbatch, int causal, const bp_opts* opts);
+
+/* Bytes of activation stash one (chunk, micro-batch) forward keeps until its backward
+ * (the M_a of Table 2 for this chunk, statistics included).  0 for a NULL handle. */
+size_t bp_stage_stash_bytes(const bp_stage_t* st);
 
 /* Synchronise the stream, free everything the object owns.  NULL is accepted. */
 int bp_stage_destroy(bp_stage_t* st);

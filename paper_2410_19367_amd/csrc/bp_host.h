@@ -83,6 +83,12 @@ struct Stage {
     std::vector<uint8_t> grad_clean[2];
     // Grouped weight gradients: per (direction, chunk) the micro-batches waiting for their group.
     int wgrad_group = 1;
+    bool lean = false;                   // stash without LN outputs and GELU output: recomputed for the weight gradients
+    // lean mode: forward scratch for a, m, g; per contraction segment the recomputed a, m, g and
+    // throw-away LayerNorm statistics for the side stream's weight-gradient GEMMs
+    void *fw_a = nullptr, *fw_m = nullptr, *fw_g = nullptr;
+    void* re_x[3][kMaxGemmSegments] = {};    // [g | m | a][segment]
+    float* re_stats = nullptr;
     bool fuse_gelu = true;               // GELU forward/backward inside the GEMM epilogues when possible
     std::vector<PendGroup> pend[2];
     std::vector<void*> pend_pool;                    // idle PendingMb buffers

@@ -126,6 +126,8 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     if (opt.dtype != BP_F32 && opt.dtype != BP_BF16) return fail(BP_EINVAL, "unknown dtype %d", opt.dtype);
     if (opt.n_chunks < 0 || opt.mlp < 0 || opt.max_inflight < 0 || opt.ln_eps < 0)
         return fail(BP_EINVAL, "negative option");
+    if (opt.stash_recompute != 0 && opt.stash_recompute != 1)
+        return fail(BP_EINVAL, "stash_recompute %d is not 0 or 1", opt.stash_recompute);
     if (opt.wgrad_group < 0 || opt.wgrad_group > kMaxGemmSegments)
         return fail(BP_EINVAL, "wgrad_group %d outside 0..%d", opt.wgrad_group, kMaxGemmSegments);
     if (opt.mlp % 8) return fail(BP_ESHAPE, "mlp width must be a multiple of 8");
@@ -144,6 +146,7 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     st->eps = opt.ln_eps > 0 ? opt.ln_eps : 1e-5f;
     st->stream = (hipStream_t)opt.hip_stream;
     st->esz = dtype_size(st->dtype);
+    st->lean = opt.stash_recompute == 1;
     st->wgrad_group = opt.wgrad_group ? opt.wgrad_group : std::min(4, std::max(1, 8192 / st->T));
     // tuning switches for A/B measurements: BITPIPE_DISABLE is a bit mask, 1: GELU fused into the
     // GEMM epilogues, 2: grouped weight gradients, 4: second stream
@@ -182,8 +185,9 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     const size_t TH = (size_t)st->T * st->H * st->esz, TF = (size_t)st->T * st->F * st->esz;
     size_t so = 0;
     auto take = [&](size_t bytes) { size_t o = so; so += align_up(bytes, 256); return o; };
-    st->s_x = take(TH); st->s_a = take(TH); st->s_qkv = take(3 * TH); st->s_ctx = take(TH);
-    st->s_y = take(TH); st->s_m = take(TH); st->s_u = take(TF); st->s_g = take(TF);
+    // lean stash: a, m and g get no room (their offsets are never used then)
+    st->s_x = take(TH); st->s_a = st->lean ? 0 : take(TH); st->s_qkv = take(3 * TH); st->s_ctx = take(TH);
+    st->s_y = take(TH); st->s_m = st->lean ? 0 : take(TH); st->s_u = take(TF); st->s_g = st->lean ? 0 : take(TF);
     st->s_mean1 = take(st->T * sizeof(float)); st->s_rstd1 = take(st->T * sizeof(float));
     st->s_mean2 = take(st->T * sizeof(float)); st->s_rstd2 = take(st->T * sizeof(float));
     st->s_lse = take((size_t)st->B * st->heads * st->S * sizeof(float));
@@ -214,6 +218,13 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
         // weight gradients with few output tiles (H x H, or a narrow MLP) and a long token axis
         st->ws_splitk_side_elems = std::min((size_t)4 * st->H * std::max(st->H, st->F), (size_t)64 << 20);
         if (!rc) rc = dev_alloc((void**)&st->ws_splitk_side, st->ws_splitk_side_elems * sizeof(float));
+    }
+    if (!rc && st->lean) {
+        (rc = dev_alloc(&st->fw_a, TH)) || (rc = dev_alloc(&st->fw_m, TH)) || (rc = dev_alloc(&st->fw_g, TF)) ||
+            (rc = dev_alloc((void**)&st->re_stats, (size_t)2 * st->T * sizeof(float)));
+        for (int i = 0; i < st->wgrad_group && !rc; ++i)
+            (rc = dev_alloc(&st->re_x[0][i], TF)) || (rc = dev_alloc(&st->re_x[1][i], TH)) ||
+                (rc = dev_alloc(&st->re_x[2][i], TH));
     }
     if (!rc) rc = dev_alloc((void**)&st->ws_delta, (size_t)st->B * st->heads * st->S * sizeof(float));
     if (rc) { delete st; return rc; }
@@ -278,6 +289,8 @@ Stage::~Stage() {
     for (auto b : ws_dx) hipFree(b);
     hipFree(ws_h4);
     hipFree(ws_splitk);
+    hipFree(fw_a); hipFree(fw_m); hipFree(fw_g); hipFree(re_stats);
+    for (auto& row : re_x) for (auto b : row) hipFree(b);
     hipFree(ws_splitk_side);
     hipFree(ws_delta);
     for (auto& kv : lens) hipFree(kv.second);
@@ -389,8 +402,8 @@ int Stage::merge_directions() {
 // ------------------------------------------------------------------ grouped weight gradients
 
 // Gradient of weight matrix k (0: W2, 1: W1, 2: Wo, 3: Wqkv) of one layer over the group's waiting
-// micro-batches plus, when cur_x is given, the current one: a single GEMM whose contraction runs
-// over all their tokens.
+// micro-batches plus, when cur_x (the current micro-batch's stash of this layer) is given, the
+// current one: a single GEMM whose contraction runs over all their tokens.
 int Stage::wgrad_one(int dir, int chunk, int l, int k, const void* cur_x, const void* cur_dy, int acc,
                      hipStream_t ss) {
     static const int ids[4] = {BP_W2, BP_W1, BP_WO, BP_WQKV};
@@ -400,15 +413,39 @@ int Stage::wgrad_one(int dir, int chunk, int l, int k, const void* cur_x, const 
     const void* xs[kMaxGemmSegments];
     const void* ys[kMaxGemmSegments];
     int n = 0;
+    // Lean stash: the operand of W2, W1 and Wqkv (GELU output, LN2 output, LN1 output) was not
+    // kept; it is rebuilt from the stashed u, y, x on this stream right before the GEMM.
+    auto operand = [&](const char* stash_layer, int seg, const void** out) -> int {
+        if (!lean || k == 2) { *out = stash_layer + sx[k]; return BP_OK; }
+        const int which = k == 0 ? 0 : k == 1 ? 1 : 2;
+        void* dst = re_x[which][seg];
+        hipError_t e;
+        if (k == 0) {
+            Scoped sc(this, BP_K_GELU_FWD, 0, 2.0 * T * F * esz);
+            e = launch_gelu_fwd(dtype, T, F, stash_layer + s_u, (const float*)param(chunk, l, BP_B1), dst, ss);
+        } else {
+            Scoped sc(this, BP_K_LN_FWD, 0, 2.0 * T * H * esz);
+            const bool second = k == 1;
+            e = launch_ln_fwd(dtype, T, H, stash_layer + (second ? s_y : s_x),
+                              (const float*)param(chunk, l, second ? BP_LN2_G : BP_LN1_G),
+                              (const float*)param(chunk, l, second ? BP_LN2_B : BP_LN1_B), eps, dst,
+                              re_stats, re_stats + T, nullptr, ss);
+        }
+        if (e != hipSuccess) return fail(BP_EHIP, "recomputing a stash tensor: %s", hipGetErrorString(e));
+        *out = dst;
+        return BP_OK;
+    };
+    int rc;
     for (const PendingMb& it : grp.items) {
         if (n >= kMaxGemmSegments) return fail(BP_ESTATE, "weight-gradient group overflow");
-        xs[n] = (const char*)slots[it.slot].buf + (size_t)l * s_layer_bytes + sx[k];
+        if ((rc = operand((const char*)slots[it.slot].buf + (size_t)l * s_layer_bytes, n, &xs[n]))) return rc;
         ys[n] = (const char*)it.buf + (size_t)l * q_layer_bytes + qy[k];
         ++n;
     }
     if (cur_x) {
         if (n >= kMaxGemmSegments) return fail(BP_ESTATE, "weight-gradient group overflow");
-        xs[n] = cur_x; ys[n] = cur_dy; ++n;
+        if ((rc = operand((const char*)cur_x, n, &xs[n]))) return rc;
+        ys[n] = cur_dy; ++n;
     }
     if (n == 0) return BP_OK;
     GemmArgs g;
@@ -596,14 +633,18 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
         char* sb = (char*)slots[slot].buf + (size_t)l * s_layer_bytes;
         const void* x = l == 0 ? act_in : (const void*)(sb + s_x);
         void* z = l == L - 1 ? act_out : (void*)(sb + s_layer_bytes + s_x);
+        // LN outputs and GELU output: kept in the stash, or scratch when they are recomputed later
+        void* a_out = lean ? fw_a : (void*)(sb + s_a);
+        void* m_out = lean ? fw_m : (void*)(sb + s_m);
+        void* g_out = lean ? fw_g : (void*)(sb + s_g);
         {   // a = LN1(x); layer 0 also keeps a copy of the caller's input for the backward
             Scoped sc(this, BP_K_LN_FWD, 0, 2 * unit);
             BP_LAUNCH(launch_ln_fwd(dtype, T, H, x, (const float*)param(chunk, l, BP_LN1_G),
-                                    (const float*)param(chunk, l, BP_LN1_B), eps, sb + s_a,
+                                    (const float*)param(chunk, l, BP_LN1_B), eps, a_out,
                                     (float*)(sb + s_mean1), (float*)(sb + s_rstd1),
                                     l == 0 ? sb + s_x : nullptr, stream));
         }
-        if ((rc = gemm(sb + s_a, H, 0, param_t(chunk, l, BP_WQKV), H, 1, sb + s_qkv, 3 * H, T, 3 * H, H,
+        if ((rc = gemm(a_out, H, 0, param_t(chunk, l, BP_WQKV), H, 1, sb + s_qkv, 3 * H, T, 3 * H, H,
                        (const float*)param(chunk, l, BP_BQKV), nullptr, 0))) return rc;
         {
             AttnArgs a{B, S, heads, d, causal ? 1 : 0, ln, sb + s_qkv, sb + s_ctx, (float*)(sb + s_lse),
@@ -616,28 +657,28 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
         {
             Scoped sc(this, BP_K_LN_FWD, 0, 2 * unit);
             BP_LAUNCH(launch_ln_fwd(dtype, T, H, sb + s_y, (const float*)param(chunk, l, BP_LN2_G),
-                                    (const float*)param(chunk, l, BP_LN2_B), eps, sb + s_m,
+                                    (const float*)param(chunk, l, BP_LN2_B), eps, m_out,
                                     (float*)(sb + s_mean2), (float*)(sb + s_rstd2), nullptr, stream));
         }
         {   // u = m W1 and g = gelu(u + b1): one kernel when the GEMM can carry the activation
             GemmArgs fg;
-            fg.A = sb + s_m; fg.B = param_t(chunk, l, BP_W1); fg.C = sb + s_u;
+            fg.A = m_out; fg.B = param_t(chunk, l, BP_W1); fg.C = sb + s_u;
             fg.bias = (const float*)param(chunk, l, BP_B1); fg.residual = nullptr;
             fg.M = T; fg.N = F; fg.K = H; fg.lda = H; fg.ldb = H; fg.ldc = F;
             fg.a_t = 0; fg.b_t = 1; fg.accumulate = 0;
-            fg.epi = EPI_GELU_FWD; fg.C2 = sb + s_g;
+            fg.epi = EPI_GELU_FWD; fg.C2 = g_out;
             if (fuse_gelu && gemm_can_fuse_epilogue(dtype, fg)) {
                 Scoped sc(this, BP_K_GEMM, 2.0 * T * (double)F * H, 0);
                 BP_LAUNCH(launch_gemm(dtype, fg, stream));
             } else {
-                if ((rc = gemm(sb + s_m, H, 0, param_t(chunk, l, BP_W1), H, 1, sb + s_u, F, T, F, H, nullptr,
+                if ((rc = gemm(m_out, H, 0, param_t(chunk, l, BP_W1), H, 1, sb + s_u, F, T, F, H, nullptr,
                                nullptr, 0))) return rc;
                 Scoped sc(this, BP_K_GELU_FWD, 0, 2.0 * T * F * esz);
                 BP_LAUNCH(launch_gelu_fwd(dtype, T, F, sb + s_u, (const float*)param(chunk, l, BP_B1),
-                                          sb + s_g, stream));
+                                          g_out, stream));
             }
         }
-        if ((rc = gemm(sb + s_g, F, 0, param_t(chunk, l, BP_W2), F, 1, z, H, T, H, F,
+        if ((rc = gemm(g_out, F, 0, param_t(chunk, l, BP_W2), F, 1, z, H, T, H, F,
                        (const float*)param(chunk, l, BP_B2), sb + s_y, 0))) return rc;
     }
     return BP_OK;
@@ -733,7 +774,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
 
         // z = y + g W2 + b2
         BP_HIP(hand_over(0));                                                                               // dz
-        if (!defer && (rc = wgrad_one(dir, chunk, l, 0, sb + s_g, dz, acc, ss))) return rc;                 // dW2
+        if (!defer && (rc = wgrad_one(dir, chunk, l, 0, sb, dz, acc, ss))) return rc;                 // dW2
         {   // du = (dz W2^T) * gelu'(u + b1) with the db1 partials: one kernel when the GEMM can carry it
             GemmArgs bg;
             bg.A = dz; bg.B = P(BP_W2); bg.C = big1; bg.bias = (const float*)P(BP_B1); bg.residual = nullptr;
@@ -751,7 +792,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
             }
         }
         BP_HIP(hand_over(1));                                                                               // du
-        if (!defer && (rc = wgrad_one(dir, chunk, l, 1, sb + s_m, big1, acc, ss))) return rc;              // dW1
+        if (!defer && (rc = wgrad_one(dir, chunk, l, 1, sb, big1, acc, ss))) return rc;              // dW1
         if ((rc = gemm(big1, F, 0, P(BP_W1), F, 1, h1, H, T, H, F, nullptr, nullptr, 0))) return rc;        // dm
         {   // dy = dz + LN2bwd(dm)
             Scoped sc(this, BP_K_LN_BWD, 0, 4 * unit);
@@ -760,7 +801,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         }
         // y = x + ctx Wo + bo
         BP_HIP(hand_over(2));                                                                               // dy
-        if (!defer && (rc = wgrad_one(dir, chunk, l, 2, sb + s_ctx, h2, acc, ss))) return rc;              // dWo
+        if (!defer && (rc = wgrad_one(dir, chunk, l, 2, sb, h2, acc, ss))) return rc;              // dWo
         if ((rc = gemm(h2, H, 0, P(BP_WO), H, 1, ws_h4, H, T, H, H, nullptr, nullptr, 0))) return rc;       // dctx
         {
             AttnArgs a{B, S, heads, d, causal ? 1 : 0, ln, sb + s_qkv, sb + s_ctx, (float*)(sb + s_lse),
@@ -770,7 +811,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         }
         // qkv = a Wqkv + bqkv
         BP_HIP(hand_over(3));                                                                               // dqkv
-        if (!defer && (rc = wgrad_one(dir, chunk, l, 3, sb + s_a, big2, acc, ss))) return rc;              // dWqkv
+        if (!defer && (rc = wgrad_one(dir, chunk, l, 3, sb, big2, acc, ss))) return rc;              // dWqkv
         if ((rc = gemm(big2, 3 * H, 0, P(BP_WQKV), 3 * H, 1, h5, H, T, H, 3 * H, nullptr, nullptr, 0))) return rc;  // da
         BP_HIP(hand_over(4));                                                                               // da
         {   // every bias and LayerNorm-parameter gradient of the layer in one batched reduction
@@ -852,6 +893,12 @@ int bp_stage_init(bp_stage_t** out, int layers, int hidden, int heads, int seq, 
 int bp_stage_init_ex(bp_stage_t** out, int layers, int hidden, int heads, int seq, int microbatch,
                      int causal, const bp_opts* opts) {
     return Stage::create((Stage**)out, layers, hidden, heads, seq, microbatch, causal, opts);
+}
+
+size_t bp_stage_stash_bytes(const bp_stage_t* st) {
+    if (!st) return 0;
+    const Stage* s_ = (const Stage*)st;
+    return (size_t)s_->L * s_->s_layer_bytes;
 }
 
 int bp_stage_destroy(bp_stage_t* st) {

@@ -46,7 +46,7 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 class GpuStage:
     """Drives one library stage object for a StageConfig."""
 
-    def __init__(self, cfg: si.StageConfig, max_inflight=0, wgrad_group=0):
+    def __init__(self, cfg: si.StageConfig, max_inflight=0, wgrad_group=0, stash_recompute=0):
         import paper_2410_19367_amd as bp
         self.bp = bp
         self.cfg = cfg
@@ -54,7 +54,7 @@ class GpuStage:
                                      cfg.causal, n_chunks=cfg.n_chunks, mlp=cfg.mlp,
                                      dtype=bp.BP_BF16 if cfg.dtype == "bf16" else bp.BP_F32,
                                      max_inflight=max_inflight, ln_eps=cfg.ln_eps,
-                                     wgrad_group=wgrad_group)
+                                     wgrad_group=wgrad_group, stash_recompute=stash_recompute)
 
     def close(self):
         if self.h is not None:
@@ -99,14 +99,15 @@ def make_oracle(cfg: si.StageConfig, params):
     return st
 
 
-def run_fwd_bwd_parity(cfg: si.StageConfig, n_micro=None, seed=0, ln_jitter=0.0, check=True, wgrad_group=0):
+def run_fwd_bwd_parity(cfg: si.StageConfig, n_micro=None, seed=0, ln_jitter=0.0, check=True, wgrad_group=0,
+                       stash_recompute=0):
     """F then B for each micro-batch on both sides; returns dict name -> rel err."""
     torch = torch_mod()
     n_micro = cfg.n_micro if n_micro is None else n_micro
     params = si.make_params(cfg, seed, ln_jitter)
     orc = make_oracle(cfg, params)
     errs = {}
-    with GpuStage(cfg, wgrad_group=wgrad_group) as g:
+    with GpuStage(cfg, wgrad_group=wgrad_group, stash_recompute=stash_recompute) as g:
         g.load_params(params)
         g.bp.bp_stage_zero_grad(g.h)
         for mb in range(n_micro):

@@ -146,3 +146,26 @@ def test_grouped_weight_gradients_interleaved_chunks_and_directions():
             for name in si.PARAM_NAMES:
                 err = hz.rel_err(g.grad(c, 0, name), orc.grads[0][c][0][name])
                 assert err <= hz.TOL[cfg.dtype], (c, name, err)
+
+
+@pytest.mark.parametrize("group", [1, 3])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_lean_stash_recomputes_ln_and_gelu_outputs(group, dtype):
+    """stash_recompute = 1 keeps 10 instead of 16 [T,H]-sized tensors per layer (Table 2's activation
+    memory M_a) and rebuilds the LayerNorm and GELU outputs for the weight gradients: same
+    activations, input gradients and accumulated gradients as the oracle, with and without
+    grouped weight gradients (five micro-batches: complete groups and a flushed remainder)."""
+    import paper_2410_19367_amd as bp
+    base = si.CONFIGS[1] if dtype == "bf16" else si.CONFIGS[0]
+    cfg = si.scaled(base, name=f"small_lean{group}", layers=2, hidden=256, heads=2, seq=128,
+                    microbatch=2, n_micro=5, dtype=dtype, causal=True)
+    hz.run_fwd_bwd_parity(cfg, ln_jitter=0.1, wgrad_group=group, stash_recompute=1)
+    with hz.GpuStage(cfg) as full, hz.GpuStage(cfg, stash_recompute=1) as lean:
+        esz = 2 if dtype == "bf16" else 4
+        T, H, F = cfg.T, cfg.hidden, cfg.F
+        saved = bp.bp_stage_stash_bytes(full.h) - bp.bp_stage_stash_bytes(lean.h)
+        assert saved == cfg.layers * (2 * T * H + T * F) * esz          # a, m and g of every layer
+        # 16 T H elements per layer plus the row statistics and the softmax log-sum-exp
+        stats = (4 * T + cfg.microbatch * cfg.heads * cfg.seq) * 4
+        assert bp.bp_stage_stash_bytes(full.h) == cfg.layers * (16 * T * H * esz + stats)
+        assert bp.bp_stage_stash_bytes(lean.h) == cfg.layers * (10 * T * H * esz + stats)
