@@ -2,14 +2,18 @@
 // three shapes of a linear layer: forward Y = X W (+b)(+res), dgrad dX = dY W^T, wgrad dW += X^T dY.
 //
 // A block computes a BM x BN tile of C, stepping over K in slices of BK = 64.  Each slice of
-// op(A) and op(B) is copied global -> registers -> LDS as 16-byte chunks with no reshaping:
+// op(A) and op(B) sits in LDS as 16-byte chunks with no reshaping:
 //   * an operand whose contraction index is contiguous in memory ("k-major": X, dY in dgrad,
-//     W in dgrad) is stored as [row][64 k] and read back with one ds_read_b128 per fragment;
-//   * an operand whose row index is contiguous ("r-major": W in forward, X^T and dY in wgrad)
-//     is stored as [k][rows] and read back with the LDS transpose read ds_read_b64_tr_b16,
-//     which hands each lane four consecutive k of one row.
+//     W in dgrad, the transposed weight copies the forward uses) is stored as [row][64 k] and read
+//     back with one ds_read_b128 per fragment;
+//   * an operand whose row index is contiguous ("r-major": X^T and dY in wgrad) is stored as
+//     [k][rows] and read back with the LDS transpose read ds_read_b64_tr_b16, which hands each
+//     lane four consecutive k of one row.
 // Both layouts XOR-swizzle the chunk index so fragment reads spread over all LDS banks.
-// Two LDS stages: the slice k+1 is written while slice k feeds the MFMAs, one barrier per slice.
+// Two kernels: gemm_mfma_kernel stages slices through registers with predication (ragged shapes);
+// gemm_dma_kernel (further down) loads them straight into LDS and carries the fused epilogues,
+// split-K and multi-segment contractions.  Two LDS stages each: slice k+1 lands while slice k
+// feeds the MFMAs, one barrier per slice.
 #include "bp_kernels.h"
 #include "bp_device.h"
 
