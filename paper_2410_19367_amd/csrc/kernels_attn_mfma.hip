@@ -15,6 +15,7 @@
 // One swizzle serves plain 16-byte fragment reads and transpose reads of the same tile:
 // chunk c of row r is stored at c ^ f(r), f chosen so that 16 consecutive rows (plain reads) and
 // 4 consecutive rows x 64 bytes (transpose reads) both cover all banks.
+#include <cstdlib>
 #include "bp_kernels.h"
 #include "bp_device.h"
 
@@ -56,28 +57,37 @@ template <int D> __device__ __forceinline__ int tile_off(int row, int chunk) {
     return row * (D * 2) + ((chunk ^ swz<D>(row)) << 4);
 }
 
-// Direct global->LDS copy of a [64][D] tile by NW waves.  gbase points at (row 0, col 0) of the
-// tile, ld is the row pitch in elements, dr the real row width.  Rows >= rows_valid are fetched from row 0 instead
-// (their values are masked or discarded by the caller), which keeps every access in bounds.
-template <int D, int NW>
-__device__ __forceinline__ void dma_tile(const bf16_t* gbase, int ld, char* lds, int wave, int lane,
-                                         int rows_valid, int dr) {
-    constexpr int CPR = D / 8;              // chunks per row
-    constexpr int NI = 64 * CPR / 64 / NW;  // wave instructions per wave
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int j = wave + NW * i;
-        const int P = j * 64 + lane;
-        int row = P / CPR;
+// Direct global->LDS copy of a [64][D] tile by NW waves.  Which 16-byte chunk a lane fetches
+// depends only on its position, so the per-lane source offsets are computed once per kernel and a
+// step only adds the tile's base address (the sequence length is a multiple of 64: every tile
+// lies inside its tensor).  dr is the real row width; with PAD, chunks beyond it come from zeros.
+template <int D, int NW, bool PAD>
+struct TilePlan {
+    static constexpr int CPR = D / 8;              // chunks per row
+    static constexpr int NI = 64 * CPR / 64 / NW;  // wave instructions per wave
+    static constexpr int ROWSTEP = NW * 64 / CPR;  // rows between a lane's consecutive chunks: a multiple
+                                                   // of 16, the period of the swizzle, so the column stays
+    int off0;                                      // element offset of the first chunk; < 0: padded column
+    int ld;                                        // row pitch in elements (wave-uniform)
+    __device__ __forceinline__ void init(int wave, int lane, int ld_, int dr) {
+        const int P = wave * 64 + lane;
+        const int row = P / CPR;
         const int c = (P % CPR) ^ swz<D>(row);
-        if (row >= rows_valid) row = 0;
-        const bf16_t* src = c * 8 < dr ? gbase + (size_t)row * ld + c * 8 : (const bf16_t*)g_zero_chunk;
-        __builtin_amdgcn_global_load_lds(
-            (const void __attribute__((address_space(1)))*)src,
-            (void __attribute__((address_space(3)))*)(lds + j * 1024), 16, 0, 0);
+        ld = ld_;
+        off0 = (!PAD || c * 8 < dr) ? row * ld + c * 8 : -1;
     }
-}
-template <int D, int NW> constexpr int dma_per_wave() { return 64 * (D / 8) / 64 / NW; }
+    // gbase points at (row 0, col 0) of the tile
+    __device__ __forceinline__ void issue(const bf16_t* gbase, char* lds, int wave) const {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const bf16_t* src = (!PAD || off0 >= 0) ? gbase + (size_t)i * ROWSTEP * ld + off0
+                                                    : (const bf16_t*)g_zero_chunk;
+            __builtin_amdgcn_global_load_lds(
+                (const void __attribute__((address_space(1)))*)src,
+                (void __attribute__((address_space(3)))*)(lds + (wave + NW * i) * 1024), 16, 0, 0);
+        }
+    }
+};
 
 // plain fragment: 8 consecutive columns (k16 step s, half h) of row (row0 + lane%32)
 template <int D>
@@ -115,7 +125,7 @@ __device__ __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 *
 // query (or key) blocks from the most expensive down, the second half from the cheapest up, so the
 // two blocks that share a CU's two slots add up to roughly the same work everywhere.
 __device__ __forceinline__ void block_coords(int nblk, int heads, bool causal, bool heavy_is_last_index,
-                                            int& blk, int& head, int& b) {
+                                            bool paired, int& blk, int& head, int& b) {
     const int per = nblk * heads;             // blocks per batch entry
     const int lin = blockIdx.x % per;
     b = blockIdx.x / per;
@@ -124,8 +134,10 @@ __device__ __forceinline__ void block_coords(int nblk, int heads, bool causal, b
     if (causal) {
         // positions 0, 1, 2, ... -> heaviest, lightest, 2nd heaviest, 2nd lightest, ... folded so that
         // the first half of the launch is the heavy half
+        // paired: for kernels with two resident blocks per CU; otherwise plain heaviest-first, which
+        // lets the hardware hand the light blocks to whichever CU finishes first
         const int half = (nblk + 1) / 2;
-        const int rank = i < half ? i : nblk - 1 - (i - half);      // 0 = heaviest
+        const int rank = !paired ? i : i < half ? i : nblk - 1 - (i - half);      // 0 = heaviest
         blk = heavy_is_last_index ? nblk - 1 - rank : rank;
     } else {
         blk = i;
@@ -133,21 +145,26 @@ __device__ __forceinline__ void block_coords(int nblk, int heads, bool causal, b
 }
 
 // =====================================================================================
-// Forward.  Block = 4 waves = 2 groups of 32 queries x 2 halves of every 64-key tile; each wave
-// keeps its own online-softmax state and the two halves are merged through LDS at the end.
+// Forward.  Block = 64 queries = 2 groups of 32 queries x (2 NT) sub-ranges of 32 keys: a step
+// covers NT tiles of 64 keys and every wave takes one half of one tile, keeping its own
+// online-softmax state; the sub-ranges are merged through LDS at the end.  NT = 1: 4 waves, 64 KB
+// (D = 128) of LDS, two blocks per CU.  NT = 2: 8 waves, 128 KB, one block per CU: the heaviest
+// causal block then needs half as many steps, and because blocks are dealt out heaviest first
+// as CUs become free the tail of the launch stays short.
 // =====================================================================================
-template <int D, bool PAD>
-__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float scale) {
-    constexpr int NW = 4, KS = D / 16, DT = D / 32;
-    constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE;   // K then V
+template <int D, bool PAD, int NT>
+__global__ __launch_bounds__(256 * NT, NT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(AttnArgs a, float scale) {
+    constexpr int NW = 4 * NT, NSUB = 2 * NT, KS = D / 16, DT = D / 32;
+    constexpr int TILE = 64 * D * 2, STAGE = NT * 2 * TILE;   // per tile: K then V
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int qg = wave >> 1, kh = wave & 1;
+    const int qg = wave / NSUB, sub = wave % NSUB;      // query group; (tile of the step, half of the tile)
+    const int tj = sub >> 1, kh = sub & 1;
     const int h = lane >> 5;
     int qblk, head, b;
-    block_coords(a.S / 64, a.heads, a.causal != 0, true, qblk, head, b);
+    block_coords(a.S / 64, a.heads, a.causal != 0, true, NT == 1, qblk, head, b);
     const int dr = PAD ? a.d : D;             // real head dimension; the guards below fold away when it equals D
     const int H = a.heads * dr, ld = 3 * H;
     const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * dr;
@@ -157,7 +174,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
     const int q_lane = q_wave + (lane & 31);
     const int klen = a.causal ? a.S : (a.lens ? a.lens[b] : a.S);
     const int kend = a.causal ? qblk * 64 + 64 : klen;     // keys [0, kend) matter to this block
-    const int nt = (kend + 63) / 64;
+    const int nt = (kend + 63) / 64;                        // tiles
+    const int nsteps = (nt + NT - 1) / NT;
     const float c = scale * kLog2e;
 
     bf16x8 qf[KS];
@@ -172,22 +190,28 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
         for (int v = 0; v < 16; ++v) ot[t][v] = 0.f;
     float m = -INFINITY, lsum = 0.f;
 
-    dma_tile<D, NW>(kbase, ld, smem, wave, lane, a.S, dr);
-    dma_tile<D, NW>(vbase, ld, smem + TILE, wave, lane, a.S, dr);
+    TilePlan<D, NW, PAD> plan;
+    plan.init(wave, lane, ld, dr);
+    auto request = [&](int step, char* st) {             // the NT tiles of a step (those that exist)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int k0 = (step * NT + j) * 64;
+            if (step * NT + j < nt) {
+                plan.issue(kbase + (size_t)k0 * ld, st + j * 2 * TILE, wave);
+                plan.issue(vbase + (size_t)k0 * ld, st + j * 2 * TILE + TILE, wave);
+            }
+        }
+    };
+    request(0, smem);
 
-    for (int t = 0; t < nt; ++t) {
-        const int k0 = t * 64;
+    for (int t = 0; t < nsteps; ++t) {
         BP_WAIT_VMCNT(0);
         __syncthreads();
-        if (t + 1 < nt) {
-            char* st = smem + ((t + 1) & 1) * STAGE;
-            const int rows = a.S - (k0 + 64);
-            dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows, dr);
-            dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows, dr);
-        }
-        const int kw = k0 + 32 * kh;                    // first key of this wave's half
-        if ((a.causal && kw > q_wave + 31) || kw >= klen) continue;     // nothing unmasked for this wave
-        const char* sk = smem + (t & 1) * STAGE;
+        if (t + 1 < nsteps) request(t + 1, smem + ((t + 1) & 1) * STAGE);
+        const int tile = t * NT + tj;
+        const int kw = tile * 64 + 32 * kh;             // first key of this wave's sub-range
+        if (tile >= nt || (a.causal && kw > q_wave + 31) || kw >= klen) continue;   // nothing unmasked for this wave
+        const char* sk = smem + (t & 1) * STAGE + tj * 2 * TILE;
         const char* sv = sk + TILE;
 
         // S^T (32 keys x 32 queries)
@@ -210,7 +234,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
             st2[v] = sv_;
             mx = fmaxf(mx, sv_);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;     // c > 0: the maximum commutes with the scaling
+        mx = halves_max(mx) * c;     // c > 0: the maximum commutes with the scaling
         // The reference point m of the running softmax only has to stay within a bounded distance of
         // the true maximum: it moves (and O, l are rescaled) only when some query of the wave sees a
         // score more than 8 binary orders above it, so p <= 2^8 and most tiles skip the rescaling.
@@ -246,37 +270,50 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(AttnArgs a, float
         }
     }
 
-    // merge the two key halves: the odd wave of each pair hands (m, l, O^T) over through LDS
-    float l = lsum + __shfl_xor(lsum, 32, 64);
+    // merge the key sub-ranges: waves 1 .. NSUB-1 of a query group hand (m, l, O^T) to wave 0 through LDS
+    float l = halves_sum(lsum);
     __syncthreads();                                    // all tile reads are over; LDS is free
-    float* xo = (float*)smem + qg * (DT * 16 * 64 + 128);   // [DT*16][64 lanes] + m[64] + l[64]
-    if (kh == 1) {
+    constexpr int XO = DT * 16 * 64 + 128;              // [DT*16][64 lanes] + m[64] + l[64]
+    float* xo = (float*)smem + (size_t)qg * (NSUB - 1) * XO;
+    if (sub != 0) {
+        float* mine = xo + (size_t)(sub - 1) * XO;
 #pragma unroll
         for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) xo[(t2 * 16 + v) * 64 + lane] = ot[t2][v];
-        xo[DT * 16 * 64 + lane] = m;
-        xo[DT * 16 * 64 + 64 + lane] = l;
+            for (int v = 0; v < 16; ++v) mine[(t2 * 16 + v) * 64 + lane] = ot[t2][v];
+        mine[DT * 16 * 64 + lane] = m;
+        mine[DT * 16 * 64 + 64 + lane] = l;
     }
     __syncthreads();
-    if (kh == 1) return;
-    const float m1 = xo[DT * 16 * 64 + lane], l1 = xo[DT * 16 * 64 + 64 + lane];
-    const float mm = fmaxf(m, m1);                      // finite: key 0 (or any valid key) is in half 0 or 1
-    const float a0 = fast_exp2(m - mm), a1 = fast_exp2(m1 - mm);
-    l = l * a0 + l1 * a1;
+    if (sub != 0) return;
+    float mm = m;                                       // finite: key 0 lies in this wave's sub-range
+#pragma unroll
+    for (int j = 0; j < NSUB - 1; ++j) mm = fmaxf(mm, xo[(size_t)j * XO + DT * 16 * 64 + lane]);
+    const float a0 = fast_exp2(m - mm);
+    l *= a0;
+#pragma unroll
+    for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) ot[t2][v] *= a0;
+#pragma unroll
+    for (int j = 0; j < NSUB - 1; ++j) {
+        const float* other = xo + (size_t)j * XO;
+        const float aj = fast_exp2(other[DT * 16 * 64 + lane] - mm);
+        l += other[DT * 16 * 64 + 64 + lane] * aj;
+#pragma unroll
+        for (int t2 = 0; t2 < DT; ++t2)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) ot[t2][v] += other[(t2 * 16 + v) * 64 + lane] * aj;
+    }
     const float inv = 1.f / l;
     bf16_t* out = (bf16_t*)a.ctx + ((size_t)b * a.S + q_lane) * H + head * dr;
 #pragma unroll
     for (int t2 = 0; t2 < DT; ++t2)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            float o4[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                o4[e] = (ot[t2][4 * g + e] * a0 + xo[(t2 * 16 + 4 * g + e) * 64 + lane] * a1) * inv;
             uint2 pk;
-            pk.x = pack_bf16x2(o4[0], o4[1]);
-            pk.y = pack_bf16x2(o4[2], o4[3]);
+            pk.x = pack_bf16x2(ot[t2][4 * g] * inv, ot[t2][4 * g + 1] * inv);
+            pk.y = pack_bf16x2(ot[t2][4 * g + 2] * inv, ot[t2][4 * g + 3] * inv);
             if (t2 * 32 + 8 * g + 4 * h < dr) *reinterpret_cast<uint2*>(out + t2 * 32 + 8 * g + 4 * h) = pk;
         }
     if (h == 0) a.lse[((size_t)b * a.heads + head) * a.S + q_lane] = (mm + log2f(l)) * kLn2;
@@ -299,7 +336,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
     const int qg = wave >> 1, kh = wave & 1;
     const int h = lane >> 5;
     int qblk, head, b;
-    block_coords(a.S / 64, a.heads, a.causal != 0, true, qblk, head, b);
+    block_coords(a.S / 64, a.heads, a.causal != 0, true, true, qblk, head, b);
     const int dr = PAD ? a.d : D;             // real head dimension; the guards below fold away when it equals D
     const int H = a.heads * dr, ld = 3 * H;
     const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * dr;
@@ -332,7 +369,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
 #pragma unroll
             for (int e = 0; e < 8; ++e) delta += (float)of[e] * (float)dof[s][e];
         }
-        delta += __shfl_xor(delta, 32, 64);
+        delta = halves_sum(delta);
         if (kh == 0 && h == 0) a.delta[li] = delta;
     }
 
@@ -342,8 +379,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
 #pragma unroll
         for (int v = 0; v < 16; ++v) dq[t][v] = 0.f;
 
-    dma_tile<D, NW>(kbase, ld, smem, wave, lane, a.S, dr);
-    dma_tile<D, NW>(vbase, ld, smem + TILE, wave, lane, a.S, dr);
+    TilePlan<D, NW, PAD> plan;
+    plan.init(wave, lane, ld, dr);
+    plan.issue(kbase, smem, wave);
+    plan.issue(vbase, smem + TILE, wave);
 
     for (int t = 0; t < nt; ++t) {
         const int k0 = t * 64;
@@ -351,9 +390,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
         __syncthreads();
         if (t + 1 < nt) {
             char* st = smem + ((t + 1) & 1) * STAGE;
-            const int rows = a.S - (k0 + 64);
-            dma_tile<D, NW>(kbase + (size_t)(k0 + 64) * ld, ld, st, wave, lane, rows, dr);
-            dma_tile<D, NW>(vbase + (size_t)(k0 + 64) * ld, ld, st + TILE, wave, lane, rows, dr);
+            plan.issue(kbase + (size_t)(k0 + 64) * ld, st, wave);
+            plan.issue(vbase + (size_t)(k0 + 64) * ld, st + TILE, wave);
         }
         const int kw = k0 + 32 * kh;
         if ((a.causal && kw > q_wave + 31) || kw >= klen) continue;
@@ -432,7 +470,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
     const int kg = wave >> 1, qh = wave & 1;
     const int h = lane >> 5;
     int kblk, head, b;
-    block_coords(a.S / 64, a.heads, a.causal != 0, false, kblk, head, b);   // key block 0 is the heaviest
+    block_coords(a.S / 64, a.heads, a.causal != 0, false, true, kblk, head, b);   // key block 0 is the heaviest
     const int dr = PAD ? a.d : D;             // real head dimension; the guards below fold away when it equals D
     const int H = a.heads * dr, ld = 3 * H;
     const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * dr;
@@ -475,10 +513,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
     const int t0 = a.causal ? kblk : 0;        // first 64-query tile that can see this block's keys
     const int nt = a.S / 64;
 
+    TilePlan<D, NW, PAD> plan_q, plan_do;
+    plan_q.init(wave, lane, ld, dr);
+    plan_do.init(wave, lane, H, dr);
     auto load_stage = [&](int t, char* st) {
         const int q0 = t * 64;
-        dma_tile<D, NW>(qkv + (size_t)q0 * ld, ld, st, wave, lane, a.S - q0, dr);
-        dma_tile<D, NW>(dobase + (size_t)q0 * H, H, st + TILE, wave, lane, a.S - q0, dr);
+        plan_q.issue(qkv + (size_t)q0 * ld, st, wave);
+        plan_do.issue(dobase + (size_t)q0 * H, st + TILE, wave);
         if (threadIdx.x < 64) ((float*)(st + 2 * TILE))[threadIdx.x] = lse[q0 + threadIdx.x] * kLog2e;
         else if (threadIdx.x < 128) ((float*)(st + 2 * TILE))[threadIdx.x] = dlt[q0 + threadIdx.x - 64];
     };
@@ -576,19 +617,33 @@ static hipError_t set_smem(K kern, size_t smem) {
     return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
 }
 
-template <int D, bool PAD>
-static hipError_t launch_fwd_t(const AttnArgs& a, hipStream_t s) {
+// tiles of 64 keys (or queries) per step: two when the sequence is long enough for the halved step
+// count to matter
+static int tiles_per_step(const AttnArgs& a) {
+    static const int forced = getenv("BP_EXP_ATTN_NT") ? atoi(getenv("BP_EXP_ATTN_NT")) : 0;
+    if (forced) return forced;
+    return a.S >= 512 ? 2 : 1;
+}
+
+template <int D, bool PAD, int NT>
+static hipError_t launch_fwd_nt(const AttnArgs& a, hipStream_t s) {
     const float scale = 1.f / sqrtf((float)a.d);
-    const dim3 grid((a.S / 64) * a.heads * a.B), block(256);
-    const size_t smem = 2 * 2 * 64 * D * 2;
+    const dim3 grid((a.S / 64) * a.heads * a.B), block(256 * NT);
+    const size_t stages = (size_t)2 * NT * 2 * 64 * D * 2;
+    const size_t merge = (size_t)2 * (2 * NT - 1) * ((D / 32) * 16 * 64 + 128) * sizeof(float);
+    const size_t smem = stages > merge ? stages : merge;
     static bool set = false;
     if (!set) {
-        hipError_t e = set_smem(attn_fwd_mfma_kernel<D, PAD>, smem);
+        hipError_t e = set_smem(attn_fwd_mfma_kernel<D, PAD, NT>, smem);
         if (e != hipSuccess) return e;
         set = true;
     }
-    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, PAD>), grid, block, smem, s, a, scale);
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, PAD, NT>), grid, block, smem, s, a, scale);
     return hipGetLastError();
+}
+template <int D, bool PAD>
+static hipError_t launch_fwd_t(const AttnArgs& a, hipStream_t s) {
+    return tiles_per_step(a) == 2 ? launch_fwd_nt<D, PAD, 2>(a, s) : launch_fwd_nt<D, PAD, 1>(a, s);
 }
 
 hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
