@@ -510,6 +510,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
 #pragma unroll
         for (int v = 0; v < 16; ++v) { dk[t][v] = 0.f; dv[t][v] = 0.f; }
 
+    const bool pad_in_block = kblk * 64 + 64 > klen;   // some of this block's keys are padding
     const int t0 = a.causal ? kblk : 0;        // first 64-query tile that can see this block's keys
     const int nt = a.S / 64;
 
@@ -546,12 +547,21 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sq, 32 * qh, s, lane), kf[s], sacc, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<D>(sdo, 32 * qh, s, lane), vf[s], dp, 0, 0, 0);
         }
+        // masked scores become -inf before the exponential (p = 0, dS = 0); both conditions are
+        // wave-uniform branches, taken only on the diagonal tile and in a block with padded keys
+        if (need_mask) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (k_lane > qw + acc_row(v, h)) sacc[v] = -INFINITY;
+        }
+        if (pad_in_block && k_lane >= klen) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sacc[v] = -INFINITY;
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int qi = acc_row(v, h);
-            float p = fast_exp2(__builtin_fmaf(sacc[v], c, -s_lse[qi]));
-            if (need_mask && k_lane > qw + qi) p = 0.f;
-            if (k_lane >= klen) p = 0.f;
+            const float p = fast_exp2(__builtin_fmaf(sacc[v], c, -s_lse[qi]));
             sacc[v] = p;                                 // P
             dp[v] = p * (dp[v] - s_dlt[qi]);             // dS
         }
