@@ -92,6 +92,9 @@ struct ColsumBatch {
     ColsumJob jobs[kMaxColsumJobs];
     int n;
     int overwrite = 0;       // 1: outputs receive = instead of +=
+    // filled by launch_colsum_batch: first column-block id of each job in the flattened grid of the
+    // partial kernel (jobs without a tensor own no blocks)
+    int first_block[kMaxColsumJobs + 1] = {};
 };
 hipError_t launch_colsum_batch(int dtype, int T, const ColsumBatch& batch, hipStream_t stream);
 

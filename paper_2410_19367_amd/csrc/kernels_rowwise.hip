@@ -114,7 +114,8 @@ __global__ __launch_bounds__(256) void ln_bwd_rows_kernel(const T* __restrict__ 
 }
 
 // ------------------------------------------------------------------ column reductions
-// Several reductions over [T, N_j] tensors run as one batch (blockIdx.z = job).  Block = 4 waves
+// Several reductions over [T, N_j] tensors run as one batch (blockIdx.x walks the column blocks of
+// all jobs, blockIdx.y the row chunks).  Block = 4 waves
 // covering 512 columns x kColsumRows rows; wave w takes rows w, w+4, ... and requests all of
 // them before consuming the first.  Partials are combined across the waves in LDS and written
 // per row chunk; a second kernel folds the chunks in a fixed order, so the result does not
@@ -122,11 +123,14 @@ __global__ __launch_bounds__(256) void ln_bwd_rows_kernel(const T* __restrict__ 
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(ColsumBatch batch, int rows) {
     __shared__ float red[2][4][576];
-    const ColsumJob job = batch.jobs[blockIdx.z];
+    // blockIdx.x runs over the column blocks of all jobs one after the other
+    int ji = 0;
+    while (ji + 1 < batch.n && (int)blockIdx.x >= batch.first_block[ji + 1]) ++ji;
+    const ColsumJob job = batch.jobs[ji];
     const int N = job.N;
+    const int cb = blockIdx.x - batch.first_block[ji];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int col = blockIdx.x * 512 + lane * 8;
-    if (blockIdx.x * 512 >= N || !job.A) return;        // uniform per block
+    const int col = cb * 512 + lane * 8;
     const T* A = (const T*)job.A;
     const T* X = (const T*)job.X;
     const bool with_x = X != nullptr;
@@ -137,6 +141,15 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(ColsumBatch batch, 
         // a wave's 8 rows in two groups of 4: all loads of a group are in flight together, and the
         // register footprint stays small enough for every block of the launch to be resident
         constexpr int RPW = kColsumRows / 4, GRP = 4;
+        float mu[RPW], rs[RPW];                          // row statistics, requested before the rows
+        if (with_x) {
+#pragma unroll
+            for (int j = 0; j < RPW; ++j) {
+                const int r = min(r0 + w + 4 * j, rows - 1);
+                mu[j] = job.mean[r];
+                rs[j] = job.rstd[r];
+            }
+        }
 #pragma unroll
         for (int j0 = 0; j0 < RPW; j0 += GRP) {
             float a[GRP][8], xv[GRP][8];
@@ -153,9 +166,8 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(ColsumBatch batch, 
                 const int r = r0 + w + 4 * (j0 + j);
                 if (r < r1) {
                     if (with_x) {
-                        const float mu = job.mean[r], rs = job.rstd[r];
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) sx[i] += a[j][i] * (xv[j][i] - mu) * rs;
+                        for (int i = 0; i < 8; ++i) sx[i] += a[j][i] * (xv[j][i] - mu[j0 + j]) * rs[j0 + j];
                     }
 #pragma unroll
                     for (int i = 0; i < 8; ++i) sa[i] += a[j][i];
@@ -173,7 +185,7 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(ColsumBatch batch, 
     const int nout = with_x ? 2 : 1;
     for (int e = threadIdx.x; e < 512 * nout; e += 256) {
         const int o = e / 512, c = e % 512;
-        const int gc = blockIdx.x * 512 + c;
+        const int gc = cb * 512 + c;
         if (gc < N) {
             const int a = (c >> 3) * 9 + (c & 7);
             const float v = (red[o][0][a] + red[o][1][a]) + (red[o][2][a] + red[o][3][a]);
@@ -427,9 +439,16 @@ hipError_t launch_colsum_batch(int dtype, int T, const ColsumBatch& batch, hipSt
         any_partial |= batch.jobs[j].A != nullptr;
     }
     if (any_partial) {
-        dim3 grid((max_n + 511) / 512, chunks, batch.n), block(256);
-        if (dtype == BF16) hipLaunchKernelGGL((colsum_partial_kernel<bf16_t>), grid, block, 0, s, batch, T);
-        else hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, block, 0, s, batch, T);
+        ColsumBatch b2 = batch;
+        int nb = 0;
+        for (int j = 0; j < batch.n; ++j) {
+            b2.first_block[j] = nb;
+            if (batch.jobs[j].A) nb += (batch.jobs[j].N + 511) / 512;
+        }
+        b2.first_block[batch.n] = nb;
+        dim3 grid(nb, chunks), block(256);
+        if (dtype == BF16) hipLaunchKernelGGL((colsum_partial_kernel<bf16_t>), grid, block, 0, s, b2, T);
+        else hipLaunchKernelGGL((colsum_partial_kernel<float>), grid, block, 0, s, b2, T);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
