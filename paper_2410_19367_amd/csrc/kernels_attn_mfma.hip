@@ -15,7 +15,6 @@
 // One swizzle serves plain 16-byte fragment reads and transpose reads of the same tile:
 // chunk c of row r is stored at c ^ f(r), f chosen so that 16 consecutive rows (plain reads) and
 // 4 consecutive rows x 64 bytes (transpose reads) both cover all banks.
-#include <cstdlib>
 #include "bp_kernels.h"
 #include "bp_device.h"
 
@@ -627,12 +626,19 @@ static hipError_t set_smem(K kern, size_t smem) {
     return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
 }
 
-// tiles of 64 keys (or queries) per step: two when the sequence is long enough for the halved step
-// count to matter
+// Tiles of 64 keys per forward step.  Two (8 waves, one block per CU) halve the step count of the
+// heaviest causal block, which is what bounds a launch with only a couple of blocks per CU; with
+// many blocks per CU the 4-wave form with two co-resident blocks is faster.
 static int tiles_per_step(const AttnArgs& a) {
-    static const int forced = getenv("BP_EXP_ATTN_NT") ? atoi(getenv("BP_EXP_ATTN_NT")) : 0;
-    if (forced) return forced;
-    return a.S >= 512 ? 2 : 1;
+    static int n_cu = 0;
+    if (!n_cu) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+            n_cu = 256;
+    }
+    const long blocks = (long)(a.S / 64) * a.heads * a.B;
+    return (a.S >= 512 && blocks <= 2L * n_cu) ? 2 : 1;
 }
 
 template <int D, bool PAD, int NT>

@@ -699,6 +699,17 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
             --splits;
         if (splits > 1 && t256 * splits >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s, splits);
     }
+    // Small outputs (fewer than 192 tiles of 128 x 128) with a long K: the same split, on the small tiles
+    const long t128 = (long)(g.M / 128) * (g.N / 128);
+    if (t128 < 192 && g.split_ws && g.epi == EPI_NONE) {
+        int splits = (int)(256 / t128);
+        if (splits > 4) splits = 4;
+        const long k_total = (long)g.K * g.nseg;
+        while (splits > 1 && (k_total % (splits * BK) || k_total / splits < 512 ||
+                              (size_t)splits * g.M * g.N > g.split_ws_elems))
+            --splits;
+        if (splits > 1) return launch_dma<128, 128, 2, 4, 2>(g, s, splits);
+    }
     // 8 waves (2 per SIMD) hide the LDS and load latencies better than 4 on these small tiles
     return launch_dma<128, 128, 2, 4, 2>(g, s);
 }

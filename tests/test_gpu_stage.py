@@ -169,3 +169,34 @@ def test_lean_stash_recomputes_ln_and_gelu_outputs(group, dtype):
         stats = (4 * T + cfg.microbatch * cfg.heads * cfg.seq) * 4
         assert bp.bp_stage_stash_bytes(full.h) == cfg.layers * (16 * T * H * esz + stats)
         assert bp.bp_stage_stash_bytes(lean.h) == cfg.layers * (10 * T * H * esz + stats)
+
+
+def _random_small_configs(n, seed):
+    """Seeded draw of small stage shapes that land on different kernel paths: aligned and ragged
+    GEMMs, head widths 32..128 (some padded), causal / padded-bidirectional, MLP widths that are
+    and are not multiples of 128, all weight-gradient group sizes, lean and full stash."""
+    import random
+    rng = random.Random(seed)
+    out = []
+    for i in range(n):
+        d = rng.choice([32, 40, 64, 96, 128])
+        heads = rng.choice([1, 2, 3, 4])
+        hidden = d * heads
+        causal = rng.random() < 0.5
+        seq = rng.choice([64, 128, 192, 100, 72]) if d in (64, 128) or rng.random() < 0.7 else rng.choice([64, 128])
+        mb = rng.choice([1, 2, 3])
+        mlp = rng.choice([4 * hidden, 2 * hidden, 3 * hidden + 8, 512])
+        kw = dict(layers=rng.choice([1, 2]), hidden=hidden, heads=heads, seq=seq, microbatch=mb, causal=causal,
+                  mlp=mlp, n_micro=rng.choice([1, 2, 3, 5]))
+        if not causal and rng.random() < 0.7:
+            kw.update(len_lo=max(1, seq // 4), len_hi=seq)
+        out.append((i, kw, rng.choice([1, 2, 3, 4]), rng.choice([0, 1])))
+    return out
+
+
+@pytest.mark.parametrize("idx,kw,group,lean", _random_small_configs(16, 20241127))
+def test_random_small_stage_configs(idx, kw, group, lean):
+    cfg = si.scaled(si.CONFIGS[1], name=f"small_rand{idx}", **kw)
+    errs = hz.run_fwd_bwd_parity(cfg, ln_jitter=0.1, wgrad_group=group, stash_recompute=lean, seed=idx)
+    worst = max(errs.items(), key=lambda kv: kv[1])
+    print(idx, kw, "group", group, "lean", lean, "worst", worst)
