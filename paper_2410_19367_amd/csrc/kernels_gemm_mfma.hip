@@ -684,7 +684,12 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     auto fill = [](long t) { return t <= 0 ? 0.0 : (double)t / (double)(((t + 255) / 256) * 256); };
     const long t192 = (g.M % 256 == 0 && g.N % 192 == 0) ? (long)(g.M / 256) * (g.N / 192) : 0;
     // (the fused GELU-backward epilogue folds column sums over power-of-two lane groups: not 96 wide)
-    if (g.epi == EPI_NONE && t192 >= 192 && 0.95 * fill(t192) > fill(t256))
+    // With both operands read through the transpose path (weight gradients) and a long contraction
+    // the 192-wide tile runs its main loop at about two thirds of the 256-wide one's rate, so it
+    // has to fill the chip that much better to win (and a grid that leaves CUs free lets the other
+    // stream's kernels in); otherwise the two are within 5 %.
+    const double rate192 = (g.a_t && !g.b_t && (long)g.K * g.nseg >= 4096) ? 0.65 : 0.95;
+    if (g.epi == EPI_NONE && t192 >= 192 && rate192 * fill(t192) > fill(t256))
         return launch_dma<256, 192, 4, 2, 2>(g, s);
     if (t256 >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s);
     // Few output tiles but a long K: 256x256 tiles on K slices keep the operand traffic per flop
