@@ -234,8 +234,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(GemmArgs g, int 
 // are produced by choosing which global chunk each lane fetches.
 // =====================================================================================
 
+// (a 16-byte fragment read serves 16 lanes = 16 consecutive rows per cycle: the XOR has to give
+// those rows 16 different chunk positions modulo the 256-byte bank period)
 template <int BKT> __device__ __forceinline__ int kmaj_swz(int row) {
-    return BKT == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+    return BKT == 128 ? (row & 15) : BKT == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 // byte offset of logical 16-byte chunk c of `row` in a k-major tile [R][BKT]
 template <int BKT> __device__ __forceinline__ int kmaj_off(int row, int c) {
@@ -606,16 +608,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int spli
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NS>
+template <int BM, int BN, int WM, int WN, int NS, int BKT = 64>
 static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1) {
     const int tiles_m = g.M / BM, tiles_n = g.N / BN;
     const dim3 grid(tiles_m * tiles_n * splits), block(WM * WN * 64);
-    const size_t stages = (size_t)NS * (BM + BN) * 64 * 2;
+    const size_t stages = (size_t)NS * (BM + BN) * BKT * 2;
     const size_t epilogue = (size_t)WM * WN * 32 * (BN / WN + 8) * sizeof(float);
     const size_t smem = stages > epilogue ? stages : epilogue;
 #define BP_GEMM_LAUNCH(AR, BR)                                                                   \
     do {                                                                                         \
-        auto kern = gemm_dma_kernel<BM, BN, WM, WN, 64, NS, AR, BR>;                             \
+        auto kern = gemm_dma_kernel<BM, BN, WM, WN, BKT, NS, AR, BR>;                            \
         static bool attr_set = false;   /* once per instantiation */                             \
         if (smem > 64 * 1024 && !attr_set) {                                                     \
             hipError_t e = hipFuncSetAttribute((const void*)kern,                                \
@@ -715,7 +717,9 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
             --splits;
         if (splits > 1) return launch_dma<128, 128, 2, 4, 2>(g, s, splits);
     }
-    // 8 waves (2 per SIMD) hide the LDS and load latencies better than 4 on these small tiles
+    // 8 waves (2 per SIMD) hide the LDS and load latencies better than 4 on these small tiles, and
+    // slices of 128 along K (two stages of 64 KB) halve the number of barriers per MFMA
+    if (g.K % 128 == 0) return launch_dma<128, 128, 2, 4, 2, 128>(g, s);
     return launch_dma<128, 128, 2, 4, 2>(g, s);
 }
 
