@@ -520,8 +520,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
         const int q0 = t * 64;
         plan_q.issue(qkv + (size_t)q0 * ld, st, wave);
         plan_do.issue(dobase + (size_t)q0 * H, st + TILE, wave);
-        if (threadIdx.x < 64) ((float*)(st + 2 * TILE))[threadIdx.x] = lse[q0 + threadIdx.x] * kLog2e;
-        else if (threadIdx.x < 128) ((float*)(st + 2 * TILE))[threadIdx.x] = dlt[q0 + threadIdx.x - 64];
+        // the tile's 64 log-sum-exp values and 64 deltas travel the same way (4 bytes per lane): a load
+        // into registers followed by an LDS store would make these waves wait for the tile loads
+        // issued just before it, i.e. for the whole memory latency, in every step
+        if (wave == 0)
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(lse + q0 + lane),
+                                             (void __attribute__((address_space(3)))*)(st + 2 * TILE), 4, 0, 0);
+        else if (wave == 1)
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(dlt + q0 + lane),
+                                             (void __attribute__((address_space(3)))*)(st + 2 * TILE + 256), 4, 0, 0);
     };
     load_stage(t0, smem + (t0 & 1) * STAGE);
 
@@ -560,7 +567,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int qi = acc_row(v, h);
-            const float p = fast_exp2(__builtin_fmaf(sacc[v], c, -s_lse[qi]));
+            const float p = fast_exp2(__builtin_fmaf(sacc[v], c, -s_lse[qi] * kLog2e));
             sacc[v] = p;                                 // P
             dp[v] = p * (dp[v] - s_dlt[qi]);             // dS
         }
