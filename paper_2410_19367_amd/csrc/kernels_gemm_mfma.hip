@@ -379,6 +379,70 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
         }
     }
 
+    constexpr int KK = BKT / 16;
+    constexpr int NREAD = (TM * (A_RMAJOR ? 2 : 1) + TN * (B_RMAJOR ? 2 : 1));   // LDS reads per k16 step
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto read_step = [&](const char* sa, int kk, int buf) {
+        const char* sb = sa + A_BYTES;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[buf][i] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 32, kk, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[buf][j] = read_frag2<BN, BKT, B_RMAJOR>(sb, wn * (BN / WN) + j * 32, kk, lane);
+    };
+    auto mfma_step = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+    };
+    auto interleave = [&]() {        // issue order: one LDS read between MFMAs until the reads are out
+#pragma unroll
+        for (int r = 0; r < NREAD; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
+        }
+    };
+
+    if (NS == 2 && KK % 2 == 0) {
+        // Two stages: the barrier between slices sits in front of the *last* k16 step of a slice, whose
+        // fragments are already in registers.  Past the barrier the first fragments of the next slice
+        // are requested and the loads of the slice after it are issued, and the MFMAs of that last
+        // step cover their latency, so no wave starts a slice with an empty matrix pipe.
+        BP_WAIT_VMCNT(0);
+        __syncthreads();
+        if (1 < nk) {
+            pa.issue(a_next, smem + STAGE, wave);
+            pb.issue(b_next, smem + STAGE + A_BYTES, wave);
+            advance();
+        }
+        read_step(smem, 0, 0);
+        for (int kt = 0; kt < nk; ++kt) {
+            const char* sa = smem + (kt & 1) * STAGE;
+#pragma unroll
+            for (int kk = 0; kk + 1 < KK; ++kk) {
+                read_step(sa, kk + 1, (kk + 1) & 1);
+                mfma_step(kk & 1);
+                interleave();
+            }
+            if (kt + 1 < nk) {
+                // every LDS read of slice kt has returned (the last ones feed the MFMAs below), the
+                // next slice has landed: publish it and free this slice's stage
+                __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0)
+                BP_WAIT_VMCNT(0);
+                __syncthreads();
+                read_step(smem + ((kt + 1) & 1) * STAGE, 0, 0);
+                if (kt + 2 < nk) {
+                    char* st = smem + (kt & 1) * STAGE;
+                    pa.issue(a_next, st, wave);
+                    pb.issue(b_next, st + A_BYTES, wave);
+                    advance();
+                }
+            }
+            mfma_step((KK - 1) & 1);
+            if (kt + 1 < nk) interleave();
+        }
+    } else {
     for (int kt = 0; kt < nk; ++kt) {
         // slice kt has landed once at most (NS-2) later slices are still in flight
         if (kt + NS - 2 < nk) { BP_WAIT_VMCNT((NS - 2) * LPT); } else { BP_WAIT_VMCNT(0); }
@@ -392,40 +456,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
             advance();
         }
         const char* sa = smem + (kt % NS) * STAGE;
-        const char* sb = sa + A_BYTES;
         // fragments are fetched one k16 step ahead of the MFMAs that use them
-        constexpr int KK = BKT / 16;
-        bf16x8 fa[2][TM], fb[2][TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[0][i] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 32, 0, lane);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[0][j] = read_frag2<BN, BKT, B_RMAJOR>(sb, wn * (BN / WN) + j * 32, 0, lane);
+        read_step(sa, 0, 0);
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            const int cb = kk & 1, nb = cb ^ 1;
-            if (kk + 1 < KK) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    fa[nb][i] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 32, kk + 1, lane);
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    fb[nb][j] = read_frag2<BN, BKT, B_RMAJOR>(sb, wn * (BN / WN) + j * 32, kk + 1, lane);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cb][i], fb[cb][j], acc[i][j], 0, 0, 0);
-            if (kk + 1 < KK) {
-                // issue order: one LDS read between MFMAs until the next step's reads are out
-                constexpr int NREAD = (TM * (A_RMAJOR ? 2 : 1) + TN * (B_RMAJOR ? 2 : 1));
-#pragma unroll
-                for (int r = 0; r < NREAD; ++r) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
-                }
-            }
+            if (kk + 1 < KK) read_step(sa, kk + 1, (kk + 1) & 1);
+            mfma_step(kk & 1);
+            if (kk + 1 < KK) interleave();
         }
+    }
     }
 
     // ---- epilogue through LDS.  The accumulators hold one column and 16 scattered rows per
