@@ -265,10 +265,11 @@ int bp_op_gemm(int dtype, int a_t, int b_t, int M, int N, int K,
  * Section 2 with the sum over micro-batches moved inside the contraction.
  * X: host array of n device pointers, each [T, M] row-major in `dtype`; dY: likewise [T, N];
  * dW: dev fp32 [M, N].  overwrite != 0: dW = instead of dW +=.
- * workspace: optional dev fp32 scratch of workspace_elems floats (NULL / 0: none).  With it, a
- * product with few output tiles and a long token axis is cut into up to 4 slices of the token axis
- * that run on different CUs; their partial sums go through the workspace (needs 4*M*N floats to
- * take effect) and are added in a fixed order.  Asynchronous on `stream`. */
+ * workspace: optional dev fp32 scratch of workspace_elems floats (NULL / 0: none).  With it, the
+ * output tiles that do not fill the chip (all of them for a small dW, else those of the last,
+ * partly filled round) are cut into up to 4 slices of a long token axis that run on different
+ * CUs; their partial sums go through the workspace (4*M*N floats always suffice) and are added
+ * in a fixed order.  Asynchronous on `stream`. */
 int bp_op_wgrad_group(int dtype, int M, int N, int T, int n, const void* const* X,
                       const void* const* dY, float* dW, int overwrite, float* workspace,
                       size_t workspace_elems, void* stream);

@@ -14,6 +14,8 @@
 // gemm_dma_kernel (further down) loads them straight into LDS and carries the fused epilogues,
 // split-K and multi-segment contractions.  Two LDS stages each: slice k+1 lands while slice k
 // feeds the MFMAs, one barrier per slice.
+#include <cstdlib>
+
 #include "bp_kernels.h"
 #include "bp_device.h"
 
@@ -303,24 +305,38 @@ constexpr int rows_per_instr(int lanes_per_row) {
     return r;
 }
 
-template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n, int splits) {
-    constexpr int NW = WM * WN;
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2, STAGE = A_BYTES + B_BYTES;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-
-    // tile order: each XCD (blocks are dealt round-robin over 8 XCDs) gets a contiguous range of
-    // ids, walked in groups of 4 tile rows so that concurrent blocks share A rows and B columns
+// Tile order: each XCD (blocks are dealt round-robin over 8 XCDs) gets a contiguous range of ids,
+// walked in groups of 4 tile rows so that concurrent blocks share A rows and B columns.
+__device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int& tm, int& tn) {
     const int nblk = tiles_m * tiles_n;
-    const int sp = blockIdx.x / nblk;                    // K slice of this block (0 when not split)
-    int t = blockIdx.x % nblk;
     if (nblk % 8 == 0) t = (t & 7) * (nblk >> 3) + (t >> 3);
     constexpr int GM = 4;
     const int per_group = GM * tiles_n;
     const int first_m = (t / per_group) * GM;
     const int gsize = min(tiles_m - first_m, GM);
-    const int tm = first_m + (t % per_group) % gsize, tn = (t % per_group) / gsize;
+    tm = first_m + (t % per_group) % gsize;
+    tn = (t % per_group) / gsize;
+}
+
+template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n, int splits,
+                                                               int n_full) {
+    constexpr int NW = WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int A_BYTES = BM * BKT * 2, B_BYTES = BN * BKT * 2, STAGE = A_BYTES + B_BYTES;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    // Blocks 0 .. n_full-1 compute whole tiles.  The remaining tiles (the tail of the launch, which
+    // would occupy only part of the chip) are cut along K: block n_full + j takes slice j / n_tail
+    // of tail tile j % n_tail and leaves an fp32 partial for the reduce kernel.
+    const int nblk = tiles_m * tiles_n;
+    const int n_tail = nblk - n_full;
+    const bool is_split = (int)blockIdx.x >= n_full;
+    const int sp = is_split ? ((int)blockIdx.x - n_full) / n_tail : 0;
+    const int tail_idx = is_split ? ((int)blockIdx.x - n_full) % n_tail : 0;
+    const int eff_splits = is_split ? splits : 1;
+    int tm, tn;
+    tile_coords(is_split ? n_full + tail_idx : (int)blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int lane = threadIdx.x & 63;
@@ -331,7 +347,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     // [sp * nk, (sp + 1) * nk) of the concatenation.  (seg, kl) is the position of the next slice
     // to request and (a_next, b_next) its tile origin.
     const int nk_seg = g.K / BKT;
-    const int nk = nk_seg * g.nseg / splits;
+    const int nk = nk_seg * g.nseg / eff_splits;
     const size_t a_step = A_RMAJOR ? (size_t)BKT * g.lda : BKT;
     const size_t b_step = B_RMAJOR ? (size_t)BKT * g.ldb : BKT;
     auto a_origin = [&](int sgm) {
@@ -485,7 +501,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
         // accumulators are staged, so their latency overlaps the LDS round trip
         constexpr int ELPR = WTN / 8, ERPI = rows_per_instr(ELPR), ENR = 32 / ERPI;
         u32x4 upre[ENR];
-        if (g.epi == EPI_GELU_BWD && splits == 1) {
+        if (g.epi == EPI_GELU_BWD && !is_split) {
 #pragma unroll
             for (int r = 0; r < ENR; ++r) {
                 const int row = r * ERPI + lane / ELPR;
@@ -501,15 +517,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
                 ep[(8 * (v >> 2) + 4 * h + (v & 3)) * PITCH + j * 32 + (lane & 31)] = acc[i][j][v];
         // rows per instruction: the largest power of two whose lanes fit in a wave (a 96-wide wave
         // tile leaves a quarter of the lanes idle here)
-        if (splits > 1) {           // fp32 partial of this K slice, row-major [M][N]
+        if (is_split) {             // fp32 partial of this K slice: [tail tile][slice][BM][BN]
             constexpr int LPR = WTN / 4, RPI = rows_per_instr(LPR);
             const int col = (lane % LPR) * 4;
-            float* slab = g.split_ws + (size_t)sp * g.M * g.N;
+            float* slab = g.split_ws + ((size_t)tail_idx * splits + sp) * (BM * BN) +
+                          (size_t)(wm * (BM / WM) + i * 32) * BN + wn * WTN;
 #pragma unroll
             for (int r = 0; r < 32; r += RPI) {
                 const int row = r + lane / LPR;
                 if (LPR * RPI < 64 && lane >= LPR * RPI) continue;
-                *reinterpret_cast<f32x4*>(slab + (size_t)(m_base + row) * g.N + n_base + col) =
+                *reinterpret_cast<f32x4*>(slab + (size_t)row * BN + col) =
                     *reinterpret_cast<const f32x4*>(ep + row * PITCH + col);
             }
         } else if (g.accumulate) {
@@ -607,50 +624,60 @@ static hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
     return hipGetLastError();
 }
 
-// Sum the split-K partials in slice order and apply the epilogue; 8 outputs per thread.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int splits) {
-    const size_t vec = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t total = (size_t)g.M * g.N / 8;
-    if (vec >= total) return;
-    const size_t e0 = vec * 8;
-    const int m = (int)(e0 / g.N), n = (int)(e0 % g.N);
+// Sum the K-slice partials of the tail tiles in slice order and apply the epilogue; 8 outputs per
+// thread, BM * BN / 2048 blocks per tile.
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int splits, int tiles_m, int tiles_n,
+                                                            int n_full) {
+    constexpr int BPT = BM * BN / 2048;                 // blocks per tile
+    const int tail_idx = blockIdx.x / BPT;
+    int tm, tn;
+    tile_coords(n_full + tail_idx, tiles_m, tiles_n, tm, tn);
+    const int v = (blockIdx.x % BPT) * 256 + threadIdx.x;      // 8-element vector inside the tile
+    const int r = v / (BN / 8), c = (v % (BN / 8)) * 8;
+    const int m = tm * BM + r, n = tn * BN + c;
+    const float* slab = g.split_ws + (size_t)tail_idx * splits * (BM * BN) + (size_t)r * BN + c;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int sp = 0; sp < splits; ++sp) {
-        float v[8];
-        load8(g.split_ws + (size_t)sp * g.M * g.N + e0, v);
+        float p[8];
+        load8(slab + (size_t)sp * (BM * BN), p);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] += v[i];
+        for (int i = 0; i < 8; ++i) acc[i] += p[i];
     }
     const size_t off = (size_t)m * g.ldc + n;
     if (g.accumulate == 2) {
         store8((float*)g.C + off, acc);
     } else if (g.accumulate) {
-        float c[8];
-        load8((const float*)g.C + off, c);
+        float cc[8];
+        load8((const float*)g.C + off, cc);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) c[i] += acc[i];
-        store8((float*)g.C + off, c);
+        for (int i = 0; i < 8; ++i) cc[i] += acc[i];
+        store8((float*)g.C + off, cc);
     } else {
         if (g.bias) {
-            float b[8];
-            load8(g.bias + n, b);
+            float bv[8];
+            load8(g.bias + n, bv);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] += b[i];
+            for (int i = 0; i < 8; ++i) acc[i] += bv[i];
         }
         if (g.residual) {
-            float r[8];
-            load8((const bf16_t*)g.residual + off, r);
+            float rs[8];
+            load8((const bf16_t*)g.residual + off, rs);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] += r[i];
+            for (int i = 0; i < 8; ++i) acc[i] += rs[i];
         }
         store8((bf16_t*)g.C + off, acc);
     }
 }
 
 template <int BM, int BN, int WM, int WN, int NS, int BKT = 64>
-static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1) {
+static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1, int n_full = -1) {
     const int tiles_m = g.M / BM, tiles_n = g.N / BN;
-    const dim3 grid(tiles_m * tiles_n * splits), block(WM * WN * 64);
+    const int nblk = tiles_m * tiles_n;
+    if (splits <= 1) { splits = 1; n_full = nblk; }
+    else if (n_full < 0) n_full = 0;                    // every tile is cut along K
+    const int n_tail = nblk - n_full;
+    const dim3 grid(n_full + n_tail * splits), block(WM * WN * 64);
     const size_t stages = (size_t)NS * (BM + BN) * BKT * 2;
     const size_t epilogue = (size_t)WM * WN * 32 * (BN / WN + 8) * sizeof(float);
     const size_t smem = stages > epilogue ? stages : epilogue;
@@ -664,7 +691,7 @@ static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1) {
             if (e != hipSuccess) return e;                                                       \
             attr_set = true;                                                                     \
         }                                                                                        \
-        hipLaunchKernelGGL(kern, grid, block, smem, s, g, tiles_m, tiles_n, splits);             \
+        hipLaunchKernelGGL(kern, grid, block, smem, s, g, tiles_m, tiles_n, splits, n_full);     \
     } while (0)
     if (!g.a_t && !g.b_t) BP_GEMM_LAUNCH(false, true);
     else if (!g.a_t && g.b_t) BP_GEMM_LAUNCH(false, false);
@@ -672,9 +699,9 @@ static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1) {
     else BP_GEMM_LAUNCH(true, false);
 #undef BP_GEMM_LAUNCH
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || splits <= 1) return e;
-    const size_t vecs = (size_t)g.M * g.N / 8;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((vecs + 255) / 256)), dim3(256), 0, s, g, splits);
+    if (e != hipSuccess || n_tail == 0) return e;
+    hipLaunchKernelGGL((splitk_reduce_kernel<BM, BN>), dim3((unsigned)(n_tail * (BM * BN / 2048))), dim3(256), 0, s,
+                       g, splits, tiles_m, tiles_n, n_full);
     return hipGetLastError();
 }
 
@@ -707,6 +734,17 @@ bool gemm_can_fuse_epilogue(int dtype, const GemmArgs& g) {
     return false;
 }
 
+static int cu_count() {
+    static int n = 0;
+    if (!n) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+    }
+    return n;
+}
+
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     auto al16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
     const bool aligned128 = dma_path_ok(g);
@@ -732,29 +770,47 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     const double rate192 = (g.a_t && !g.b_t && (long)g.K * g.nseg >= 4096) ? 0.65 : 0.95;
     if (g.epi == EPI_NONE && t192 >= 192 && rate192 * fill(t192) > fill(t256))
         return launch_dma<256, 192, 4, 2, 2>(g, s);
-    if (t256 >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s);
+    // How many K slices the last, partly filled round of 256 x 256 tiles is cut into so that it fills
+    // the chip too (at most 4, each at least 1024 deep so that the fp32 partials stay a small part of
+    // the traffic).  With fewer tiles than CUs this is plain split-K.
+    const int ncu = cu_count();
+    const long k_total = (long)g.K * g.nseg;
+    auto tail_splits = [&](long tail) {
+        int splits = tail > 0 ? (int)(ncu / tail) : 1;
+        if (splits > 4) splits = 4;
+        while (splits > 1 && (k_total % (splits * BK) || k_total / splits < 1024 ||
+                              (size_t)splits * tail * 65536 > g.split_ws_elems))
+            --splits;
+        return splits;
+    };
+    if (t256 >= 192) {
+        // tuning switch for A/B measurements: bit 3 of BITPIPE_DISABLE keeps the last round whole
+        static const bool split_tail = [] {
+            const char* dis = getenv("BITPIPE_DISABLE");
+            return !(dis && (strtol(dis, nullptr, 0) & 8));
+        }();
+        const long full = (t256 / ncu) * ncu, tail = t256 - full;
+        const int splits =
+            (split_tail && g.split_ws && g.epi == EPI_NONE && tail * 4 < 3L * ncu) ? tail_splits(tail) : 1;
+        if (splits > 1) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, (int)full);
+        return launch_dma<256, 256, 4, 2, 2>(g, s);
+    }
     // Few output tiles but a long K: 256x256 tiles on K slices keep the operand traffic per flop
     // at the large-tile level (128x128 tiles are bound by the per-CU load path) and still give
-    // every CU a block.  Slices stay >= 1024 deep so the partial traffic remains small.
+    // every CU a block.
     if (t256 > 0 && g.split_ws && g.epi == EPI_NONE) {
-        int splits = (int)(256 / t256);
-        if (splits > 4) splits = 4;
-        const long k_total = (long)g.K * g.nseg;
-        while (splits > 1 && (k_total % (splits * BK) || k_total / splits < 1024 ||
-                              (size_t)splits * g.M * g.N > g.split_ws_elems))
-            --splits;
-        if (splits > 1 && t256 * splits >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s, splits);
+        const int splits = tail_splits(t256);
+        if (splits > 1 && t256 * splits >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, 0);
     }
     // Small outputs (fewer than 192 tiles of 128 x 128) with a long K: the same split, on the small tiles
     const long t128 = (long)(g.M / 128) * (g.N / 128);
     if (t128 < 192 && g.split_ws && g.epi == EPI_NONE) {
         int splits = (int)(256 / t128);
         if (splits > 4) splits = 4;
-        const long k_total = (long)g.K * g.nseg;
         while (splits > 1 && (k_total % (splits * BK) || k_total / splits < 512 ||
                               (size_t)splits * g.M * g.N > g.split_ws_elems))
             --splits;
-        if (splits > 1) return launch_dma<128, 128, 2, 4, 2>(g, s, splits);
+        if (splits > 1) return launch_dma<128, 128, 2, 4, 2>(g, s, splits, 0);
     }
     // 8 waves (2 per SIMD) hide the LDS and load latencies better than 4 on these small tiles, and
     // slices of 128 along K (two stages of 64 KB) halve the number of barriers per MFMA

@@ -254,6 +254,7 @@ def test_attention_wide_score_range(B, S, heads, d, causal):
     (2048, 2048, 1024, 4),     # with a workspace: 64 tiles x 4 token slices, one per segment
     (2048, 2048, 2048, 2),     # with a workspace: 4 token slices, two per segment
     (2048, 2048, 1536, 2),     # with a workspace: 3072 tokens -> 3 slices, boundaries inside segments
+    (4096, 5120, 2048, 2),     # with a workspace: 320 tiles, the last 64 cut into 4 token slices
 ])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("overwrite", [0, 1])
