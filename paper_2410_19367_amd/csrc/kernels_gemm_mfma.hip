@@ -802,14 +802,17 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
         const int splits = tail_splits(t256);
         if (splits > 1 && t256 * splits >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, 0);
     }
-    // Small outputs (fewer than 192 tiles of 128 x 128) with a long K: the same split, on the small tiles
+    // Small outputs (fewer than 192 tiles of 128 x 128) with a long K: the same split, on the small
+    // tiles (slices at least 1024 deep: below that the second kernel costs what the split gains)
     const long t128 = (long)(g.M / 128) * (g.N / 128);
     if (t128 < 192 && g.split_ws && g.epi == EPI_NONE) {
+        const int bk = g.K % 128 == 0 ? 128 : BK;
         int splits = (int)(256 / t128);
         if (splits > 4) splits = 4;
-        while (splits > 1 && (k_total % (splits * BK) || k_total / splits < 512 ||
+        while (splits > 1 && (k_total % (splits * bk) || k_total / splits < 1024 ||
                               (size_t)splits * g.M * g.N > g.split_ws_elems))
             --splits;
+        if (splits > 1 && bk == 128) return launch_dma<128, 128, 2, 4, 2, 128>(g, s, splits, 0);
         if (splits > 1) return launch_dma<128, 128, 2, 4, 2>(g, s, splits, 0);
     }
     // 8 waves (2 per SIMD) hide the LDS and load latencies better than 4 on these small tiles, and
