@@ -343,11 +343,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction
     const int wm = wave / WN, wn = wave % WN;
 
-    // The contraction runs over g.nseg operand pairs of g.K each; this block owns slices
-    // [sp * nk, (sp + 1) * nk) of the concatenation.  (seg, kl) is the position of the next slice
+    // The contraction runs over g.nseg operand pairs of g.K each; this block owns steps
+    // [k_first, k_first + nk) of the concatenation.  (seg, kl) is the position of the next slice
     // to request and (a_next, b_next) its tile origin.
     const int nk_seg = g.K / BKT;
-    const int nk = nk_seg * g.nseg / eff_splits;
+    const int nk_all = nk_seg * g.nseg;
+    // K slices of a split tile differ by at most one step: the first nk_all % splits get one more
+    const int nk = nk_all / eff_splits + (sp < nk_all % eff_splits ? 1 : 0);
+    const int k_first = sp * (nk_all / eff_splits) + min(sp, nk_all % eff_splits);
     const size_t a_step = A_RMAJOR ? (size_t)BKT * g.lda : BKT;
     const size_t b_step = B_RMAJOR ? (size_t)BKT * g.ldb : BKT;
     auto a_origin = [&](int sgm) {
@@ -358,7 +361,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
         const bf16_t* Bp = (const bf16_t*)(sgm == 0 ? g.B : sgm == 1 ? g.B_more[0] : sgm == 2 ? g.B_more[1] : g.B_more[2]);
         return B_RMAJOR ? Bp + n0 : Bp + (size_t)n0 * g.ldb;
     };
-    int seg = (sp * nk) / nk_seg, kl = (sp * nk) % nk_seg;
+    int seg = k_first / nk_seg, kl = k_first % nk_seg;
     const bf16_t* a_next = a_origin(seg) + kl * a_step;
     const bf16_t* b_next = b_origin(seg) + kl * b_step;
     auto advance = [&]() {
@@ -755,12 +758,15 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
             return launch_cfg<128, 128, 2, 2, true>(h, st);
         });
     }
-    // 256 x 256 tiles (8 waves) once they fill at least three quarters of the 256 CUs
+    const int ncu = cu_count();
+    const long k_total = (long)g.K * g.nseg;
+    const long most = 3L * ncu / 4;       // a launch with at least this many blocks is taken to fill the chip
+    // 256 x 256 tiles (8 waves) once they fill at least three quarters of the CUs
     const bool aligned256 = g.M % 256 == 0 && g.N % 256 == 0;
     const long t256 = aligned256 ? (long)(g.M / 256) * (g.N / 256) : 0;
     // 256 x 192 tiles when they fill the CUs better: e.g. N = 6144 gives 24 columns of 256 (192 tiles
     // for M = 2048, a quarter of the CUs idle) but 32 columns of 192 (256 tiles)
-    auto fill = [](long t) { return t <= 0 ? 0.0 : (double)t / (double)(((t + 255) / 256) * 256); };
+    auto fill = [&](long t) { return t <= 0 ? 0.0 : (double)t / (double)(((t + ncu - 1) / ncu) * ncu); };
     const long t192 = (g.M % 256 == 0 && g.N % 192 == 0) ? (long)(g.M / 256) * (g.N / 192) : 0;
     // (the fused GELU-backward epilogue folds column sums over power-of-two lane groups: not 96 wide)
     // With both operands read through the transpose path (weight gradients) and a long contraction
@@ -768,22 +774,18 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     // has to fill the chip that much better to win (and a grid that leaves CUs free lets the other
     // stream's kernels in); otherwise the two are within 5 %.
     const double rate192 = (g.a_t && !g.b_t && (long)g.K * g.nseg >= 4096) ? 0.65 : 0.95;
-    if (g.epi == EPI_NONE && t192 >= 192 && rate192 * fill(t192) > fill(t256))
+    if (g.epi == EPI_NONE && t192 >= most && rate192 * fill(t192) > fill(t256))
         return launch_dma<256, 192, 4, 2, 2>(g, s);
     // How many K slices the last, partly filled round of 256 x 256 tiles is cut into so that it fills
     // the chip too (at most 4, each at least 1024 deep so that the fp32 partials stay a small part of
-    // the traffic).  With fewer tiles than CUs this is plain split-K.
-    const int ncu = cu_count();
-    const long k_total = (long)g.K * g.nseg;
+    // the traffic; the slices need not be equal).  With fewer tiles than CUs this is plain split-K.
     auto tail_splits = [&](long tail) {
         int splits = tail > 0 ? (int)(ncu / tail) : 1;
         if (splits > 4) splits = 4;
-        while (splits > 1 && (k_total % (splits * BK) || k_total / splits < 1024 ||
-                              (size_t)splits * tail * 65536 > g.split_ws_elems))
-            --splits;
+        while (splits > 1 && (k_total / splits < 1024 || (size_t)splits * tail * 65536 > g.split_ws_elems)) --splits;
         return splits;
     };
-    if (t256 >= 192) {
+    if (t256 >= most) {
         // tuning switch for A/B measurements: bit 3 of BITPIPE_DISABLE keeps the last round whole
         static const bool split_tail = [] {
             const char* dis = getenv("BITPIPE_DISABLE");
@@ -791,27 +793,25 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
         }();
         const long full = (t256 / ncu) * ncu, tail = t256 - full;
         const int splits =
-            (split_tail && g.split_ws && g.epi == EPI_NONE && tail * 4 < 3L * ncu) ? tail_splits(tail) : 1;
+            (split_tail && g.split_ws && g.epi == EPI_NONE && tail < most) ? tail_splits(tail) : 1;
         if (splits > 1) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, (int)full);
         return launch_dma<256, 256, 4, 2, 2>(g, s);
     }
     // Few output tiles but a long K: 256x256 tiles on K slices keep the operand traffic per flop
-    // at the large-tile level (128x128 tiles are bound by the per-CU load path) and still give
-    // every CU a block.
+    // at the large-tile level (128x128 tiles are bound by the per-CU load path); measured to win
+    // from five eighths of the CUs on.
     if (t256 > 0 && g.split_ws && g.epi == EPI_NONE) {
         const int splits = tail_splits(t256);
-        if (splits > 1 && t256 * splits >= 192) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, 0);
+        if (splits > 1 && t256 * splits * 8 >= 5L * ncu) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, 0);
     }
-    // Small outputs (fewer than 192 tiles of 128 x 128) with a long K: the same split, on the small
+    // Small outputs (128 x 128 tiles on fewer than three quarters of the CUs) with a long K: the same split, on the small
     // tiles (slices at least 1024 deep: below that the second kernel costs what the split gains)
     const long t128 = (long)(g.M / 128) * (g.N / 128);
-    if (t128 < 192 && g.split_ws && g.epi == EPI_NONE) {
+    if (t128 < most && g.split_ws && g.epi == EPI_NONE) {
         const int bk = g.K % 128 == 0 ? 128 : BK;
-        int splits = (int)(256 / t128);
+        int splits = (int)(ncu / t128);
         if (splits > 4) splits = 4;
-        while (splits > 1 && (k_total % (splits * bk) || k_total / splits < 1024 ||
-                              (size_t)splits * g.M * g.N > g.split_ws_elems))
-            --splits;
+        while (splits > 1 && (k_total / splits < 1024 || (size_t)splits * g.M * g.N > g.split_ws_elems)) --splits;
         if (splits > 1 && bk == 128) return launch_dma<128, 128, 2, 4, 2, 128>(g, s, splits, 0);
         if (splits > 1) return launch_dma<128, 128, 2, 4, 2>(g, s, splits, 0);
     }

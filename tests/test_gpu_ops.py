@@ -257,6 +257,8 @@ def test_attention_wide_score_range(B, S, heads, d, causal):
     (4096, 5120, 2048, 2),     # with a workspace: 320 tiles, the last 64 cut into 4 token slices
     (512, 768, 1024, 2),       # with a workspace: 24 tiles of 128 x 128, two token slices, K steps of 128
     (512, 768, 1088, 2),       # the same with K steps of 64 (1088 = 17 * 64)
+    (2048, 2560, 1664, 2),     # with a workspace: 80 tiles x 3 token slices of 18, 17, 17 steps
+    (512, 768, 1600, 2),       # with a workspace: 24 small tiles x 3 token slices of 17, 17, 16 steps
 ])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("overwrite", [0, 1])
