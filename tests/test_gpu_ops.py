@@ -259,6 +259,7 @@ def test_attention_wide_score_range(B, S, heads, d, causal):
     (512, 768, 1088, 2),       # the same with K steps of 64 (1088 = 17 * 64)
     (2048, 2560, 1664, 2),     # with a workspace: 80 tiles x 3 token slices of 18, 17, 17 steps
     (512, 768, 1600, 2),       # with a workspace: 24 small tiles x 3 token slices of 17, 17, 16 steps
+    (2048, 1152, 2048, 2),     # with a workspace, N a multiple of 128 and 192 but not of 256
 ])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("overwrite", [0, 1])
