@@ -24,10 +24,12 @@ struct GemmArgs {
     int lda, ldb, ldc;
     int a_t, b_t;
     int accumulate;          // 1: C is fp32 and receives +=;  2: C is fp32 and is overwritten (= instead of +=)
-    // optional split-K workspace (fp32, split_ws_elems floats).  When given, a GEMM whose output
-    // has too few 256x256 tiles to fill the chip may cut K into slices computed by different
-    // blocks, each writing an fp32 partial there; a second kernel adds the partials in a fixed
-    // order and applies the epilogue.  Null: never split.
+    // optional split-K workspace (fp32, split_ws_elems floats).  When given, the output tiles that
+    // would leave much of the chip idle (all of them when they are few, else those of a partly
+    // filled last round) may have K cut into up to 4 slices computed by different blocks, each
+    // writing an fp32 partial of its tile there; a second kernel adds the partials in a fixed
+    // order and applies the epilogue.  splits * tiles * tile size floats are needed; 4 * M * N
+    // always suffice.  Null: never split.
     float* split_ws = nullptr;
     size_t split_ws_elems = 0;
     // Optional further contraction segments: the product runs over nseg operand pairs
