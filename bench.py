@@ -105,6 +105,8 @@ def main():
     ap.add_argument("--stash-recompute", action="store_true",
                     help="stage configs: keep 10 instead of 16 [T,H] tensors per layer in the stash and "
                          "recompute the LayerNorm / GELU outputs for the weight gradients")
+    ap.add_argument("--wgrad-group", type=int, default=0,
+                    help="micro-batches per grouped weight-gradient GEMM (0: the library's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for FETCH_SIZE / WRITE_SIZE counters)")
@@ -146,7 +148,8 @@ def main():
 
     st = bp.bp_stage_init_ex(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, cfg.causal,
                              n_chunks=1, mlp=cfg.mlp, dtype=bp.BP_BF16 if cfg.dtype == "bf16" else bp.BP_F32,
-                             max_inflight=2, ln_eps=cfg.ln_eps, stash_recompute=int(args.stash_recompute))
+                             max_inflight=2, ln_eps=cfg.ln_eps, stash_recompute=int(args.stash_recompute),
+                             wgrad_group=args.wgrad_group)
     params = si.make_params(cfg)
     for l in range(cfg.layers):
         for name, tid in bp.TENSOR_IDS.items():

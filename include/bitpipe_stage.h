@@ -70,7 +70,7 @@ typedef struct bp_opts {
     int wgrad_group;    /* weight gradients of this many consecutive backward calls of a chunk
                            and direction are computed together (one pass over the fp32
                            accumulator instead of one per micro-batch); 1: each call computes
-                           its own; 2..4; 0 -> min(4, max(1, 8192 / (microbatch*seq))).  A
+                           its own; 2..8; 0 -> min(8, max(1, 16384 / (microbatch*seq))).  A
                            group keeps the stashes of its waiting micro-batches (beyond
                            max_inflight) plus their output gradients until it is complete or
                            until bp_stage_get_grad / bp_run_schedule's merge flushes it.      */
@@ -260,7 +260,7 @@ int bp_op_gemm(int dtype, int a_t, int b_t, int M, int N, int K,
                const void* A, int lda, const void* B, int ldb, void* C, int ldc,
                const float* bias, const void* residual, int accumulate, void* stream);
 
-/* Weight gradient of a linear map over a group of n micro-batches (1 <= n <= 4) in one pass over
+/* Weight gradient of a linear map over a group of n micro-batches (1 <= n <= 8) in one pass over
  * the fp32 accumulator: dW (+)= sum_i X[i]^T dY[i], the synchronous gradient accumulation of
  * Section 2 with the sum over micro-batches moved inside the contraction.
  * X: host array of n device pointers, each [T, M] row-major in `dtype`; dY: likewise [T, N];

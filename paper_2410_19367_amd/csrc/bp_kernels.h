@@ -11,7 +11,7 @@ enum DType { F32 = 0, BF16 = 1 };
 
 inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
 
-constexpr int kMaxGemmSegments = 4;
+constexpr int kMaxGemmSegments = 8;
 
 // C = op(A) op(B) (+bias) (+residual)  or  C(fp32) += op(A) op(B).
 //   op(A)[m,k] = a_t ? A[k*lda + m] : A[m*lda + k]

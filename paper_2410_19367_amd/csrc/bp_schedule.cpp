@@ -298,6 +298,19 @@ int Stage::run_schedule(const Layout& L, const bp_op* order, int n_ops, int D, c
     if (slot_capacity < n_stage * N) slot_capacity = n_stage * N;
 
     if ((rc = zero_grad())) return rc;
+    // A weight-gradient group that the iteration cannot fill would only be flushed at the end, with
+    // nothing left to overlap it: no group larger than the backward calls a (direction, stage) gets.
+    struct GroupCap {
+        Stage* s; int saved;
+        ~GroupCap() { s->wgrad_group = saved; }
+    } cap{this, wgrad_group};
+    {
+        std::vector<int> calls(2 * (size_t)n_stage, 0);
+        for (int i = 0; i < n_ops; ++i)
+            if (order[i].kind == 1) ++calls[(size_t)order[i].dir * n_stage + order[i].stage];
+        for (int c : calls)
+            if (c > 0 && c < wgrad_group) wgrad_group = c;
+    }
     const int last = n_stage - 1;
     const float scale = 1.f / ((float)N * (float)B * (float)S);
     for (int i = 0; i < n_ops; ++i) {

@@ -147,7 +147,7 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     st->stream = (hipStream_t)opt.hip_stream;
     st->esz = dtype_size(st->dtype);
     st->lean = opt.stash_recompute == 1;
-    st->wgrad_group = opt.wgrad_group ? opt.wgrad_group : std::min(4, std::max(1, 8192 / st->T));
+    st->wgrad_group = opt.wgrad_group ? opt.wgrad_group : std::min(kMaxGemmSegments, std::max(1, 16384 / st->T));
     // tuning switches for A/B measurements: BITPIPE_DISABLE is a bit mask, 1: GELU fused into the
     // GEMM epilogues, 2: grouped weight gradients, 4: second stream (8: read by the GEMM launcher)
     if (const char* dis = getenv("BITPIPE_DISABLE")) {

@@ -354,11 +354,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     const size_t a_step = A_RMAJOR ? (size_t)BKT * g.lda : BKT;
     const size_t b_step = B_RMAJOR ? (size_t)BKT * g.ldb : BKT;
     auto a_origin = [&](int sgm) {
-        const bf16_t* A = (const bf16_t*)(sgm == 0 ? g.A : sgm == 1 ? g.A_more[0] : sgm == 2 ? g.A_more[1] : g.A_more[2]);
+        const bf16_t* A = (const bf16_t*)(sgm == 0 ? g.A : g.A_more[sgm - 1]);
         return A_RMAJOR ? A + m0 : A + (size_t)m0 * g.lda;
     };
     auto b_origin = [&](int sgm) {
-        const bf16_t* Bp = (const bf16_t*)(sgm == 0 ? g.B : sgm == 1 ? g.B_more[0] : sgm == 2 ? g.B_more[1] : g.B_more[2]);
+        const bf16_t* Bp = (const bf16_t*)(sgm == 0 ? g.B : g.B_more[sgm - 1]);
         return B_RMAJOR ? Bp + n0 : Bp + (size_t)n0 * g.ldb;
     };
     int seg = k_first / nk_seg, kl = k_first % nk_seg;

@@ -249,6 +249,8 @@ def test_attention_wide_score_range(B, S, heads, d, causal):
     (2048, 6144, 192, 3),      # 256x192 tiles
     (4096, 4096, 128, 4),      # 256x256 tiles, four segments of two slices
     (256, 256, 64, 4),         # one slice per segment
+    (256, 256, 64, 8),         # the most segments
+    (2048, 2048, 128, 8),      # 256x256 tiles, eight segments of two slices
     (200, 264, 136, 3),        # ragged: one launch per segment
     (512, 768, 256, 1),
     (2048, 2048, 1024, 4),     # with a workspace: 64 tiles x 4 token slices, one per segment

@@ -104,15 +104,16 @@ def test_zero_grad_semantics_across_iterations():
                 assert not g.grad(1, l, name).any(), ("chunk 1 never ran", l, name)
 
 
-@pytest.mark.parametrize("group", [1, 2, 3, 4])
+@pytest.mark.parametrize("group,n_micro", [(1, 5), (2, 5), (3, 5), (4, 5), (5, 5), (8, 5), (8, 9)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_grouped_weight_gradients(group, dtype):
-    """Weight gradients computed over groups of 1..4 backward calls: five micro-batches give
-    complete groups plus a remainder that only the gradient read-out flushes; activations,
-    input gradients and all accumulated gradients must match the oracle either way."""
+def test_grouped_weight_gradients(group, n_micro, dtype):
+    """Weight gradients computed over groups of 1..8 backward calls: the micro-batches give
+    complete groups plus a remainder (or no complete group at all) that only the gradient
+    read-out flushes; activations, input gradients and all accumulated gradients must match the
+    oracle either way."""
     base = si.CONFIGS[1] if dtype == "bf16" else si.CONFIGS[0]
-    cfg = si.scaled(base, name=f"small_group{group}", layers=2, hidden=256, heads=2, seq=128,
-                    microbatch=2, n_micro=5, dtype=dtype, causal=True)
+    cfg = si.scaled(base, name=f"small_group{group}_{n_micro}", layers=2, hidden=256, heads=2, seq=128,
+                    microbatch=2, n_micro=n_micro, dtype=dtype, causal=True)
     hz.run_fwd_bwd_parity(cfg, ln_jitter=0.1, wgrad_group=group)
 
 
@@ -148,7 +149,7 @@ def test_grouped_weight_gradients_interleaved_chunks_and_directions():
                 assert err <= hz.TOL[cfg.dtype], (c, name, err)
 
 
-@pytest.mark.parametrize("group", [1, 3])
+@pytest.mark.parametrize("group", [1, 3, 5])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_lean_stash_recomputes_ln_and_gelu_outputs(group, dtype):
     """stash_recompute = 1 keeps 10 instead of 16 [T,H]-sized tensors per layer (Table 2's activation
