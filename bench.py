@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # launches), from the hardware-counter passes over this same workload; counters cannot be read
 # from inside this process, so the figure is carried over from
 # profiles/stage_fwd_bwd_cfg1_pmc_counters.md.  Workloads without such a profile report null.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"cfg1_gpt_h2048": 223.5e6}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"cfg1_gpt_h2048": 228.6e6}
 
 
 def bench_schedule(args, cfg, bp, si, torch, np):
