@@ -73,7 +73,9 @@ typedef struct bp_opts {
                            its own; 2..8; 0 -> min(8, max(1, 16384 / (microbatch*seq))).  A
                            group keeps the stashes of its waiting micro-batches (beyond
                            max_inflight) plus their output gradients until it is complete or
-                           until bp_stage_get_grad / bp_run_schedule's merge flushes it.      */
+                           until bp_stage_get_grad / bp_run_schedule's merge flushes it.
+                           bp_run_schedule uses groups no larger than the number of backward
+                           calls a (direction, stage) gets in the iteration.                  */
     int stash_recompute;/* 0: the stash keeps everything the backward reads, 16*T*H elements per
                            layer (x, LN1 out, qkv, ctx, y, LN2 out, u, GELU out); 1: the two
                            LayerNorm outputs and the GELU output are not kept (10*T*H per layer)
