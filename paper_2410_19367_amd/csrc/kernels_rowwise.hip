@@ -206,7 +206,9 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(ColsumBatch batch, in
     for (int o = 0; o < nout; ++o) {
         float s = 0.f;
         if (c < N) {
-#pragma unroll 4
+            // 16 loads in flight per thread (the additions keep their order): with 4 the kernel
+            // spends its time waiting for one memory latency after the other
+#pragma unroll 16
             for (int k = slice; k < chunks; k += 4) s += job.part[((size_t)k * nout + o) * N + c];
         }
         red[slice][cl] = s;
