@@ -151,7 +151,7 @@ __device__ __forceinline__ void block_coords(int nblk, int heads, bool causal, b
 // causal block then needs half as many steps, and because blocks are dealt out heaviest first
 // as CUs become free the tail of the launch stays short.
 // =====================================================================================
-template <int D, bool PAD, int NT>
+template <int D, int DR, int NT>
 __global__ __launch_bounds__(256 * NT, NT == 1 ? 2 : 1) void attn_fwd_mfma_kernel(AttnArgs a, float scale) {
     constexpr int NW = 4 * NT, NSUB = 2 * NT, KS = D / 16, DT = D / 32;
     constexpr int TILE = 64 * D * 2, STAGE = NT * 2 * TILE;   // per tile: K then V
@@ -164,7 +164,10 @@ __global__ __launch_bounds__(256 * NT, NT == 1 ? 2 : 1) void attn_fwd_mfma_kerne
     const int h = lane >> 5;
     int qblk, head, b;
     block_coords(a.S / 64, a.heads, a.causal != 0, true, NT == 1, qblk, head, b);
-    const int dr = PAD ? a.d : D;             // real head dimension; the guards below fold away when it equals D
+    // real head dimension: the tile width (no padding, every guard below folds away), a fixed narrower
+    // width (the guards fold to constants), or with DR = 0 whatever the call says
+    constexpr bool PAD = DR != D;
+    const int dr = DR ? DR : a.d;
     const int H = a.heads * dr, ld = 3 * H;
     const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * dr;
     const bf16_t* kbase = qkv + H;
@@ -324,7 +327,7 @@ __global__ __launch_bounds__(256 * NT, NT == 1 ? 2 : 1) void attn_fwd_mfma_kerne
 //   dQ^T (D x 32) += K^T dS^T         (K tile read plainly for S^T and transposed for dQ^T)
 // The two halves' partial dQ^T are added through LDS at the end.
 // =====================================================================================
-template <int D, bool PAD>
+template <int D, int DR>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, float scale) {
     constexpr int NW = 4, KS = D / 16, DT = D / 32;
     constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE;
@@ -336,7 +339,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
     const int h = lane >> 5;
     int qblk, head, b;
     block_coords(a.S / 64, a.heads, a.causal != 0, true, true, qblk, head, b);
-    const int dr = PAD ? a.d : D;             // real head dimension; the guards below fold away when it equals D
+    // real head dimension: the tile width (no padding, every guard below folds away), a fixed narrower
+    // width (the guards fold to constants), or with DR = 0 whatever the call says
+    constexpr bool PAD = DR != D;
+    const int dr = DR ? DR : a.d;
     const int H = a.heads * dr, ld = 3 * H;
     const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * dr;
     const bf16_t* kbase = qkv + H;
@@ -458,7 +464,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_mfma_kernel(AttnArgs a, fl
 //   dV^T (D x 32 keys) += dO^T P,   dK^T (D x 32 keys) += Q^T dS
 // The two query halves' partial sums are added through LDS at the end.
 // =====================================================================================
-template <int D, bool PAD>
+template <int D, int DR>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, float scale) {
     constexpr int NW = 4, KS = D / 16, DT = D / 32;
     constexpr int TILE = 64 * D * 2, STAGE = 2 * TILE + 512;   // Q, dO, then lse[64], delta[64]
@@ -470,7 +476,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_mfma_kernel(AttnArgs a, f
     const int h = lane >> 5;
     int kblk, head, b;
     block_coords(a.S / 64, a.heads, a.causal != 0, false, true, kblk, head, b);   // key block 0 is the heaviest
-    const int dr = PAD ? a.d : D;             // real head dimension; the guards below fold away when it equals D
+    // real head dimension: the tile width (no padding, every guard below folds away), a fixed narrower
+    // width (the guards fold to constants), or with DR = 0 whatever the call says
+    constexpr bool PAD = DR != D;
+    const int dr = DR ? DR : a.d;
     const int H = a.heads * dr, ld = 3 * H;
     const bf16_t* qkv = (const bf16_t*)a.qkv + (size_t)b * a.S * ld + head * dr;
     const bf16_t* dobase = (const bf16_t*)a.dctx + (size_t)b * a.S * H + head * dr;
@@ -648,7 +657,7 @@ static int tiles_per_step(const AttnArgs& a) {
     return (a.S >= 512 && blocks <= 2L * n_cu) ? 2 : 1;
 }
 
-template <int D, bool PAD, int NT>
+template <int D, int DR, int NT>
 static hipError_t launch_fwd_nt(const AttnArgs& a, hipStream_t s) {
     const float scale = 1.f / sqrtf((float)a.d);
     const dim3 grid((a.S / 64) * a.heads * a.B), block(256 * NT);
@@ -657,45 +666,50 @@ static hipError_t launch_fwd_nt(const AttnArgs& a, hipStream_t s) {
     const size_t smem = stages > merge ? stages : merge;
     static bool set = false;
     if (!set) {
-        hipError_t e = set_smem(attn_fwd_mfma_kernel<D, PAD, NT>, smem);
+        hipError_t e = set_smem(attn_fwd_mfma_kernel<D, DR, NT>, smem);
         if (e != hipSuccess) return e;
         set = true;
     }
-    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, PAD, NT>), grid, block, smem, s, a, scale);
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, DR, NT>), grid, block, smem, s, a, scale);
     return hipGetLastError();
 }
-template <int D, bool PAD>
+template <int D, int DR>
 static hipError_t launch_fwd_t(const AttnArgs& a, hipStream_t s) {
-    return tiles_per_step(a) == 2 ? launch_fwd_nt<D, PAD, 2>(a, s) : launch_fwd_nt<D, PAD, 1>(a, s);
+    return tiles_per_step(a) == 2 ? launch_fwd_nt<D, DR, 2>(a, s) : launch_fwd_nt<D, DR, 1>(a, s);
 }
 
 hipError_t launch_attn_fwd_mfma(const AttnArgs& a, hipStream_t s) {
-    if (a.d == 128) return launch_fwd_t<128, false>(a, s);
-    if (a.d == 64) return launch_fwd_t<64, false>(a, s);
-    return a.d > 64 ? launch_fwd_t<128, true>(a, s) : launch_fwd_t<64, true>(a, s);
+    if (a.d == 128) return launch_fwd_t<128, 128>(a, s);
+    if (a.d == 64) return launch_fwd_t<64, 64>(a, s);
+    // the head widths of the paper's own models (Table 3) get kernels with the width built in
+    if (a.d == 96) return launch_fwd_t<128, 96>(a, s);
+    if (a.d == 40) return launch_fwd_t<64, 40>(a, s);
+    return a.d > 64 ? launch_fwd_t<128, 0>(a, s) : launch_fwd_t<64, 0>(a, s);
 }
 
-template <int D, bool PAD>
+template <int D, int DR>
 static hipError_t launch_bwd_t(const AttnArgs& a, hipStream_t s) {
     const float scale = 1.f / sqrtf((float)a.d);
     const dim3 grid((a.S / 64) * a.heads * a.B), block(256);
     const size_t smem = 2 * 2 * 64 * D * 2, smem2 = 2 * (2 * 64 * D * 2 + 512);
     static bool set = false;
     if (!set) {
-        hipError_t e = set_smem(attn_bwd_dq_mfma_kernel<D, PAD>, smem);
-        if (e == hipSuccess) e = set_smem(attn_bwd_dkv_mfma_kernel<D, PAD>, smem2);
+        hipError_t e = set_smem(attn_bwd_dq_mfma_kernel<D, DR>, smem);
+        if (e == hipSuccess) e = set_smem(attn_bwd_dkv_mfma_kernel<D, DR>, smem2);
         if (e != hipSuccess) return e;
         set = true;
     }
-    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, PAD>), grid, block, smem, s, a, scale);
-    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, PAD>), grid, block, smem2, s, a, scale);
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, DR>), grid, block, smem, s, a, scale);
+    hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, DR>), grid, block, smem2, s, a, scale);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_bwd_mfma(const AttnArgs& a, hipStream_t s) {
-    if (a.d == 128) return launch_bwd_t<128, false>(a, s);
-    if (a.d == 64) return launch_bwd_t<64, false>(a, s);
-    return a.d > 64 ? launch_bwd_t<128, true>(a, s) : launch_bwd_t<64, true>(a, s);
+    if (a.d == 128) return launch_bwd_t<128, 128>(a, s);
+    if (a.d == 64) return launch_bwd_t<64, 64>(a, s);
+    if (a.d == 96) return launch_bwd_t<128, 96>(a, s);
+    if (a.d == 40) return launch_bwd_t<64, 40>(a, s);
+    return a.d > 64 ? launch_bwd_t<128, 0>(a, s) : launch_bwd_t<64, 0>(a, s);
 }
 
 }  // namespace bp

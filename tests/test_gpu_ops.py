@@ -157,6 +157,9 @@ ATTN_CASES = [
     (1, 128, 2, 112, False, None),
     (1, 128, 2, 48, True, None),
     (1, 64, 2, 8, True, None),
+    # long enough for the eight-wave forward (two tiles per step), padded widths
+    (1, 512, 2, 112, True, None),
+    (1, 512, 2, 40, False, [300]),
 ]
 
 
