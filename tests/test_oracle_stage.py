@@ -193,6 +193,104 @@ def test_linear_steps_match_loop_nest():
     np.testing.assert_allclose(c["h1"][0], h1, rtol=1e-13)
 
 
+def _loop_linear(x, W, b, res):
+    """y[t][o] = sum_i x[t][i] W[i][o] + b[o] + res[t][o], output-column-major loop order, python floats."""
+    T, I = len(x), len(x[0])
+    Oo = len(W[0])
+    y = [[0.0] * Oo for _ in range(T)]
+    for o in range(Oo):
+        for i in range(I):
+            w = float(W[i][o])
+            for t in range(T):
+                y[t][o] += float(x[t][i]) * w
+    for t in range(T):
+        for o in range(Oo):
+            y[t][o] += (float(b[o]) if b is not None else 0.0) + (float(res[t][o]) if res is not None else 0.0)
+    return np.array(y)
+
+
+def test_linear_primitives_match_scalar_loops_and_adjoint_identity():
+    """linear_fwd / linear_dgrad / linear_wgrad, the expected values of every GEMM parity case,
+    pinned three ways that do not call a matmul: (1) scalar loop nests in another loop order over
+    non-square shapes (a transposed or swapped operand cannot even be evaluated or gives other
+    numbers), (2) the adjoint identity <dy, x W> = <dy W^T, x> = <x^T dy, W>, (3) one-hot inputs
+    that read single rows / columns of W."""
+    rng = np.random.default_rng(40)
+    T, I, Oo = 5, 3, 7                      # all different: every transposition changes a shape
+    x = rng.standard_normal((T, I)); W = rng.standard_normal((I, Oo))
+    b = rng.standard_normal(Oo); res = rng.standard_normal((T, Oo)); dy = rng.standard_normal((T, Oo))
+    # (1) forward, with and without bias / residual
+    np.testing.assert_allclose(O.linear_fwd(x, W), _loop_linear(x, W, None, None), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(O.linear_fwd(x, W, b, res), _loop_linear(x, W, b, res), rtol=1e-13, atol=1e-13)
+    # dgrad: dx[t][i] = sum_o dy[t][o] W[i][o]   (loop order i, t, o)
+    dx = np.zeros((T, I))
+    for i in range(I):
+        for t in range(T):
+            acc = 0.0
+            for o in range(Oo):
+                acc += float(dy[t, o]) * float(W[i, o])
+            dx[t, i] = acc
+    got_dx = O.linear_dgrad(dy, W)
+    assert got_dx.shape == (T, I)
+    np.testing.assert_allclose(got_dx, dx, rtol=1e-13, atol=1e-13)
+    # wgrad: dW[i][o] = sum_t x[t][i] dy[t][o], db[o] = sum_t dy[t][o]   (loop order t outermost)
+    dW = np.zeros((I, Oo)); db = np.zeros(Oo)
+    for t in range(T):
+        for o in range(Oo):
+            db[o] += float(dy[t, o])
+            for i in range(I):
+                dW[i, o] += float(x[t, i]) * float(dy[t, o])
+    got_dW, got_db = O.linear_wgrad(x, dy)
+    assert got_dW.shape == (I, Oo) and got_db.shape == (Oo,)
+    np.testing.assert_allclose(got_dW, dW, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(got_db, db, rtol=1e-13, atol=1e-13)
+    # a leading batch axis is flattened into tokens
+    x3 = rng.standard_normal((2, T, I)); dy3 = rng.standard_normal((2, T, Oo))
+    gW3, gb3 = O.linear_wgrad(x3, dy3)
+    np.testing.assert_allclose(gW3, sum(O.linear_wgrad(x3[i], dy3[i])[0] for i in range(2)), rtol=1e-13)
+    np.testing.assert_allclose(gb3, dy3.sum(axis=(0, 1)), rtol=1e-13)
+    # (2) adjoint identity, evaluated with element-wise sums only
+    lhs = float((dy * O.linear_fwd(x, W)).sum())
+    assert abs(lhs - float((got_dx * x).sum())) < 1e-12 * max(1.0, abs(lhs))
+    assert abs(lhs - float((got_dW * W).sum())) < 1e-12 * max(1.0, abs(lhs))
+    # (3) one-hot probes: a unit input row picks a row of W, a unit output gradient picks W's column
+    for i in range(I):
+        e = np.zeros((1, I)); e[0, i] = 1.0
+        np.testing.assert_array_equal(O.linear_fwd(e, W)[0], W[i])
+    for o in range(Oo):
+        e = np.zeros((1, Oo)); e[0, o] = 1.0
+        np.testing.assert_array_equal(O.linear_dgrad(e, W)[0], W[:, o])
+    # the finite-difference meaning of the three: d<R, x W + b>/dx, /dW, /db
+    R = rng.standard_normal((T, Oo)); h = 1e-6
+    f = lambda xv, Wv, bv: float((R * O.linear_fwd(xv, Wv, bv)).sum())
+    gW, gb = O.linear_wgrad(x, R)
+    for idx in [(0, 0), (2, 5), (1, 6)]:
+        Wp = W.copy(); Wp[idx] += h; Wm = W.copy(); Wm[idx] -= h
+        assert abs((f(x, Wp, b) - f(x, Wm, b)) / (2 * h) - gW[idx]) < 1e-7
+    for idx in [(0, 0), (4, 2)]:
+        xp = x.copy(); xp[idx] += h; xm = x.copy(); xm[idx] -= h
+        assert abs((f(xp, W, b) - f(xm, W, b)) / (2 * h) - O.linear_dgrad(R, W)[idx]) < 1e-7
+    bp_ = b.copy(); bp_[3] += h; bm_ = b.copy(); bm_[3] -= h
+    assert abs((f(x, W, bp_) - f(x, W, bm_)) / (2 * h) - gb[3]) < 1e-7
+
+
+def test_linear_pins_catch_a_transposed_operand():
+    """Planted mistakes (on the CPU, in copies of the oracle's formulas): with square shapes a
+    transposed weight or swapped wgrad operands still evaluate, and the scalar-loop pin rejects them."""
+    rng = np.random.default_rng(41)
+    T = I = Oo = 4
+    x = rng.standard_normal((T, I)); W = rng.standard_normal((I, Oo)); dy = rng.standard_normal((T, Oo))
+    good = _loop_linear(x, W, None, None)
+    assert np.max(np.abs(O.linear_fwd(x, W) - good)) < 1e-12
+    assert np.max(np.abs(O.linear_fwd(x, W.T) - good)) > 1e-2          # weight read as [out, in]
+    ref_dx = np.array([[sum(dy[t, o] * W[i, o] for o in range(Oo)) for i in range(I)] for t in range(T)])
+    assert np.max(np.abs(O.linear_dgrad(dy, W) - ref_dx)) < 1e-12
+    assert np.max(np.abs(O.linear_dgrad(dy, W.T) - ref_dx)) > 1e-2     # forgot the transpose in dgrad
+    ref_dW = np.array([[sum(x[t, i] * dy[t, o] for t in range(T)) for o in range(Oo)] for i in range(I)])
+    assert np.max(np.abs(O.linear_wgrad(x, dy)[0] - ref_dW)) < 1e-12
+    assert np.max(np.abs(O.linear_wgrad(dy, x)[0] - ref_dW)) > 1e-2    # operands swapped: dW^T
+
+
 # ------------------------------------------------------------------ finite differences
 
 def _make_stage(rng, L, H, heads, S, B, causal, n_chunks=1, F=0):
