@@ -288,6 +288,22 @@ int bp_op_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* x
                         const void* residual_grad, void* dx, float* dgamma, float* dbeta,
                         float* workspace, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): bp_op_layernorm_bwd without the workspace argument.  The
+ * column-reduction partials go to a device array that is part of the library image:
+ * bp_static_scratch_floats() floats (8 MiB) per GPU, held from the library's first use of that GPU
+ * until the process ends.  Needs (T + 31) / 32 * 2 * H floats; larger problems return BP_ESHAPE
+ * (use bp_op_layernorm_bwd with a workspace).  The call makes no hipMalloc / hipFree and calls no
+ * allocating routine; it looks the array's device address up once per device (the device current
+ * at the call).  All calls on one GPU share the array: calls that overlap on one GPU (two streams,
+ * two threads) race, calls on one stream are ordered.  Nothing in it needs clearing between calls.
+ * Arguments, results and errors otherwise as bp_op_layernorm_bwd. */
+size_t bp_static_scratch_floats(void);
+int bp_op_layernorm_bwd_static(int dtype, int T, int H, const void* dout, const void* x,
+                               const float* mean, const float* rstd, const float* gamma,
+                               const void* residual_grad, void* dx, float* dgamma, float* dbeta,
+                               void* stream);
+
 /* g = GELU_tanh(u + bias) over [T,F]. */
 int bp_op_bias_gelu_fwd(int dtype, int T, int F, const void* u, const float* bias, void* g,
                         void* stream);

@@ -30,6 +30,7 @@ EXPORTS = (
     "bp_schedule_generate_ex", "bp_schedule_validate_ex", "bp_schedule_simulate_ex", "bp_run_schedule_ex",
     "bp_schedule_hops", "bp_prof_enable",
     "bp_prof_get", "bp_op_gemm", "bp_op_wgrad_group", "bp_op_layernorm_fwd", "bp_op_layernorm_bwd",
+    "bp_op_layernorm_bwd_static", "bp_static_scratch_floats",
     "bp_op_bias_gelu_fwd", "bp_op_bias_gelu_bwd", "bp_op_colsum_workspace",
     "bp_op_attention_fwd", "bp_op_attention_bwd", "bp_last_error", "bp_version",
 )
@@ -102,6 +103,8 @@ def lib():
                                         C.c_size_t, vp]
         l.bp_op_layernorm_fwd.argtypes = [ci, ci, ci, vp, vp, vp, cf, vp, vp, vp, vp]
         l.bp_op_layernorm_bwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        l.bp_op_layernorm_bwd_static.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        l.bp_static_scratch_floats.restype = C.c_size_t
         l.bp_op_bias_gelu_fwd.argtypes = [ci, ci, ci, vp, vp, vp, vp]
         l.bp_op_bias_gelu_bwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp]
         l.bp_op_colsum_workspace.argtypes = [ci, ci]
@@ -320,6 +323,17 @@ def bp_op_layernorm_bwd(dtype, T, H, dout, x, mean, rstd, gamma, residual_grad, 
     return _check(lib().bp_op_layernorm_bwd(dtype, T, H, _ptr(dout), _ptr(x), _ptr(mean), _ptr(rstd),
                                             _ptr(gamma), _ptr(residual_grad), _ptr(dx), _ptr(dgamma),
                                             _ptr(dbeta), _ptr(workspace), stream))
+
+
+def bp_op_layernorm_bwd_static(dtype, T, H, dout, x, mean, rstd, gamma, residual_grad, dx, dgamma, dbeta,
+                               stream=None):
+    return _check(lib().bp_op_layernorm_bwd_static(dtype, T, H, _ptr(dout), _ptr(x), _ptr(mean), _ptr(rstd),
+                                                   _ptr(gamma), _ptr(residual_grad), _ptr(dx), _ptr(dgamma),
+                                                   _ptr(dbeta), stream))
+
+
+def bp_static_scratch_floats() -> int:
+    return lib().bp_static_scratch_floats()
 
 
 def bp_op_bias_gelu_fwd(dtype, T, F, u, bias, g, stream=None):

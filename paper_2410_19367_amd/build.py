@@ -14,6 +14,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = [
     "bp_stage.cpp", "bp_schedule.cpp", "bp_ops.cpp", "bp_dispatch.cpp",
     "kernels_rowwise.hip", "kernels_generic.hip", "kernels_gemm_mfma.hip", "kernels_attn_mfma.hip",
+    "bp_static_scratch.hip",
 ]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
