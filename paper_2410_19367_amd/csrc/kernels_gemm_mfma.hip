@@ -389,16 +389,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-#pragma unroll
-    for (int s = 0; s < NS - 1; ++s) {
-        if (s < nk) {
-            pa.issue(a_next, smem + s * STAGE, wave);
-            pb.issue(b_next, smem + s * STAGE + A_BYTES, wave);
-            advance();
-        }
-    }
-
     constexpr int KK = BKT / 16;
+    static_assert(KK >= 2 && KK % 2 == 0, "a K slice is an even number of k16 steps");
+    static_assert((NS - 2) * LPT < 64, "outstanding loads must fit the vmcnt field");
     constexpr int NREAD = (TM * (A_RMAJOR ? 2 : 1) + TN * (B_RMAJOR ? 2 : 1));   // LDS reads per k16 step
     bf16x8 fa[2][TM], fb[2][TN];
     auto read_step = [&](const char* sa, int kk, int buf) {
@@ -422,68 +415,64 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
         }
     };
+    // wait until at most `n` of the most recently requested slices are still on their way
+    auto wait_slices = [&](int n) {
+        if (NS > 4 && n >= 3) { BP_WAIT_VMCNT(3 * LPT); }
+        else if (NS > 3 && n == 2) { BP_WAIT_VMCNT(2 * LPT); }
+        else if (NS > 2 && n == 1) { BP_WAIT_VMCNT(1 * LPT); }
+        else { BP_WAIT_VMCNT(0); }
+    };
+    static_assert(NS >= 2 && NS <= 5, "2 to 5 LDS stages");
 
-    if (NS == 2 && KK % 2 == 0) {
-        // Two stages: the barrier between slices sits in front of the *last* k16 step of a slice, whose
-        // fragments are already in registers.  Past the barrier the first fragments of the next slice
-        // are requested and the loads of the slice after it are issued, and the MFMAs of that last
-        // step cover their latency, so no wave starts a slice with an empty matrix pipe.
-        BP_WAIT_VMCNT(0);
-        __syncthreads();
-        if (1 < nk) {
-            pa.issue(a_next, smem + STAGE, wave);
-            pb.issue(b_next, smem + STAGE + A_BYTES, wave);
-            advance();
-        }
-        read_step(smem, 0, 0);
-        for (int kt = 0; kt < nk; ++kt) {
-            const char* sa = smem + (kt & 1) * STAGE;
+    // NS stages: while slice kt feeds the MFMAs, slices kt+1 .. kt+NS-1 are landing or have landed.
+    // The barrier between slices sits in front of the *last* k16 step of a slice, whose fragments are
+    // already in registers.  Past the barrier the first fragments of the next slice are requested and
+    // the loads of slice kt+NS are issued into the stage just freed, and the MFMAs of that last step
+    // cover their latency, so no wave starts a slice with an empty matrix pipe.
 #pragma unroll
-            for (int kk = 0; kk + 1 < KK; ++kk) {
-                read_step(sa, kk + 1, (kk + 1) & 1);
-                mfma_step(kk & 1);
-                interleave();
-            }
-            if (kt + 1 < nk) {
-                // every LDS read of slice kt has returned (the last ones feed the MFMAs below), the
-                // next slice has landed: publish it and free this slice's stage
-                __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0)
-                BP_WAIT_VMCNT(0);
-                __syncthreads();
-                read_step(smem + ((kt + 1) & 1) * STAGE, 0, 0);
-                if (kt + 2 < nk) {
-                    char* st = smem + (kt & 1) * STAGE;
-                    pa.issue(a_next, st, wave);
-                    pb.issue(b_next, st + A_BYTES, wave);
-                    advance();
-                }
-            }
-            mfma_step((KK - 1) & 1);
-            if (kt + 1 < nk) interleave();
-        }
-    } else {
-    for (int kt = 0; kt < nk; ++kt) {
-        // slice kt has landed once at most (NS-2) later slices are still in flight
-        if (kt + NS - 2 < nk) { BP_WAIT_VMCNT((NS - 2) * LPT); } else { BP_WAIT_VMCNT(0); }
-        // the barrier publishes slice kt and retires every read of slice kt-1, whose stage the
-        // next loads overwrite
-        __syncthreads();
-        if (kt + NS - 1 < nk) {
-            char* st = smem + ((kt + NS - 1) % NS) * STAGE;
-            pa.issue(a_next, st, wave);
-            pb.issue(b_next, st + A_BYTES, wave);
+    for (int s = 0; s < NS - 1; ++s) {
+        if (s < nk) {
+            pa.issue(a_next, smem + s * STAGE, wave);
+            pb.issue(b_next, smem + s * STAGE + A_BYTES, wave);
             advance();
-        }
-        const char* sa = smem + (kt % NS) * STAGE;
-        // fragments are fetched one k16 step ahead of the MFMAs that use them
-        read_step(sa, 0, 0);
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            if (kk + 1 < KK) read_step(sa, kk + 1, (kk + 1) & 1);
-            mfma_step(kk & 1);
-            if (kk + 1 < KK) interleave();
         }
     }
+    wait_slices(min(nk, NS - 1) - 1);                   // slice 0 has landed
+    __syncthreads();
+    if (NS - 1 < nk) {
+        pa.issue(a_next, smem + (NS - 1) * STAGE, wave);
+        pb.issue(b_next, smem + (NS - 1) * STAGE + A_BYTES, wave);
+        advance();
+    }
+    read_step(smem, 0, 0);
+    int cur = 0;                                        // stage of slice kt
+    for (int kt = 0; kt < nk; ++kt) {
+        const char* sa = smem + cur * STAGE;
+#pragma unroll
+        for (int kk = 0; kk + 1 < KK; ++kk) {
+            read_step(sa, kk + 1, (kk + 1) & 1);
+            mfma_step(kk & 1);
+            interleave();
+        }
+        if (kt + 1 < nk) {
+            // every LDS read of slice kt has returned (the last ones feed the MFMAs below) and this
+            // wave's part of slice kt+1 has landed: the barrier publishes that slice and frees the
+            // stage of slice kt
+            __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0)
+            wait_slices(min(nk, kt + NS) - (kt + 2));
+            __syncthreads();
+            const int nxt = cur + 1 == NS ? 0 : cur + 1;
+            read_step(smem + nxt * STAGE, 0, 0);
+            if (kt + NS < nk) {
+                char* st = smem + cur * STAGE;
+                pa.issue(a_next, st, wave);
+                pb.issue(b_next, st + A_BYTES, wave);
+                advance();
+            }
+            cur = nxt;
+        }
+        mfma_step((KK - 1) & 1);
+        if (kt + 1 < nk) interleave();
     }
 
     // ---- epilogue through LDS.  The accumulators hold one column and 16 scattered rows per

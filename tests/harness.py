@@ -100,8 +100,12 @@ def make_oracle(cfg: si.StageConfig, params):
 
 
 def run_fwd_bwd_parity(cfg: si.StageConfig, n_micro=None, seed=0, ln_jitter=0.0, check=True, wgrad_group=0,
-                       stash_recompute=0):
-    """F then B for each micro-batch on both sides; returns dict name -> rel err."""
+                       stash_recompute=0, sync_each=True, grad_layers=None):
+    """F then B for each micro-batch on both sides; returns dict name -> rel err.
+    sync_each=False: the GPU side runs all its micro-batches back to back with no device
+    synchronisation in between (the call pattern bench.py times: consecutive calls overlap on the
+    library's two streams); its outputs are kept on the device and compared afterwards.
+    grad_layers: layers whose parameter gradients are compared (default: all)."""
     torch = torch_mod()
     n_micro = cfg.n_micro if n_micro is None else n_micro
     params = si.make_params(cfg, seed, ln_jitter)
@@ -110,21 +114,41 @@ def run_fwd_bwd_parity(cfg: si.StageConfig, n_micro=None, seed=0, ln_jitter=0.0,
     with GpuStage(cfg, wgrad_group=wgrad_group, stash_recompute=stash_recompute) as g:
         g.load_params(params)
         g.bp.bp_stage_zero_grad(g.h)
+        kept = []
+        if not sync_each:
+            ins = []
+            for mb in range(n_micro):
+                lens = si.make_seqlens(cfg, mb, seed)
+                if lens is not None:
+                    g.bp.bp_stage_set_seqlens(g.h, mb, lens)
+                ins.append((to_dev(si.make_activation(cfg, "act_in", mb, seed), cfg.dtype),
+                            to_dev(si.make_activation(cfg, "grad_out", mb, seed), cfg.dtype)))
+            torch.cuda.synchronize()
+            for mb in range(n_micro):
+                z = g.forward(0, mb, ins[mb][0])
+                dx = g.backward(0, mb, ins[mb][1])
+                kept.append((z, dx))
+            torch.cuda.synchronize()
         for mb in range(n_micro):
             x = si.make_activation(cfg, "act_in", mb, seed)
             go = si.make_activation(cfg, "grad_out", mb, seed)
             lens = si.make_seqlens(cfg, mb, seed)
             if lens is not None:
-                g.bp.bp_stage_set_seqlens(g.h, mb, lens)
+                if sync_each:
+                    g.bp.bp_stage_set_seqlens(g.h, mb, lens)
                 orc.set_seqlens(mb, lens)
-            z = g.forward(0, mb, to_dev(x, cfg.dtype))
-            dx = g.backward(0, mb, to_dev(go, cfg.dtype))
-            torch.cuda.synchronize()
+            if sync_each:
+                z = g.forward(0, mb, to_dev(x, cfg.dtype))
+                dx = g.backward(0, mb, to_dev(go, cfg.dtype))
+                torch.cuda.synchronize()
+            else:
+                z, dx = kept[mb]
             z_ref = orc.forward(0, mb, x)
             dx_ref = orc.backward(0, mb, go)
             errs[f"act_out[{mb}]"] = rel_err(to_host(z), z_ref)
             errs[f"grad_in[{mb}]"] = rel_err(to_host(dx), dx_ref)
-        for l in range(cfg.layers):
+            print(f"  parity {cfg.name}: micro-batch {mb} compared", flush=True)
+        for l in (range(cfg.layers) if grad_layers is None else grad_layers):
             for name in si.PARAM_NAMES:
                 errs[f"grad[{l}].{name}"] = rel_err(g.grad(0, l, name), orc.get_grad(0, l, name))
     if check:

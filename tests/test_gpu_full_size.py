@@ -1,10 +1,23 @@
-"""GPU parity at the baseline's full shapes, in the launch configuration bench.py times: the
-oracle runs whole micro-batches at full size (tens of seconds of fp64 numpy per case), so every
-output element and every gradient is compared, not a sample."""
+"""GPU parity at the baseline's full shapes, in the launch configuration bench.py times.
+
+What runs at full size against the oracle (fp64 numpy, tens of seconds per micro-batch):
+  * cfg1: all 8 micro-batches back to back with no synchronisation in between and the library's
+    default weight-gradient group (8), so the grouped weight-gradient GEMMs (8 contraction
+    segments, 16384 tokens, on the second stream) are compared at the shape the bench times;
+  * cfg2: 4 of its 8 micro-batches, which completes one default group (4) the same way;
+  * cfg3: one micro-batch through both layers against the oracle (the group is flushed by the
+    gradient read), plus a self-consistency check on the GPU that 4 micro-batches grouped by 4
+    give the same gradients as the same 4 computed one by one (the oracle would need about five
+    minutes for them), plus the grouped weight-gradient GEMM alone at cfg3's shapes on sampled
+    rows and columns of the oracle's result;
+  * cfg4: the whole V-schedule iteration; cfg5 / cfg6: two layers of the paper-shaped stages."""
+import functools
+
 import numpy as np
 import pytest
 
 import synth_inputs as si
+from oracle import stage_oracle as O
 from tests import harness as hz
 from tests.test_gpu_schedule import _run_iteration
 
@@ -16,25 +29,118 @@ def _report(tag, errs):
     print(tag, "worst:", [(k, f"{v:.2e}") for k, v in worst], flush=True)
 
 
-def test_cfg1_gpt_h2048_two_microbatches():
-    """4 layers, H 2048, 16 heads, S 2048, B 1, causal: forward, backward and the fp32
-    accumulation of two micro-batches against the oracle's sum."""
-    errs = hz.run_fwd_bwd_parity(si.CONFIGS[1], n_micro=2)
+def test_cfg1_gpt_h2048_all_microbatches_default_group():
+    """4 layers, H 2048, 16 heads, S 2048, B 1, causal: the bench's step, i.e. all 8 micro-batches
+    forward+backward without a device synchronisation in between, weight gradients in one group of
+    8 (the library's default at T = 2048), against the oracle's fp64 sum over the micro-batches."""
+    errs = hz.run_fwd_bwd_parity(si.CONFIGS[1], n_micro=8, sync_each=False)
     _report("cfg1", errs)
 
 
-def test_cfg2_bert_h1024_padded():
-    """6 layers, H 1024, 16 heads (d 64), S 512, B 8, key padding 256..512."""
-    errs = hz.run_fwd_bwd_parity(si.CONFIGS[2], n_micro=1)
+def test_cfg2_bert_h1024_padded_one_full_group():
+    """6 layers, H 1024, 16 heads (d 64), S 512, B 8, key padding 256..512: 4 micro-batches back to
+    back complete one default weight-gradient group (4 at T = 4096)."""
+    errs = hz.run_fwd_bwd_parity(si.CONFIGS[2], n_micro=4, sync_each=False)
     _report("cfg2", errs)
 
 
-def test_cfg3_gpt_h5120_one_layer():
-    """H 5120, 40 heads, MLP 20480, S 2048, B 2 at full width; one of the config's two layers
-    (the second layer repeats the same kernels on the same shapes)."""
-    cfg = si.scaled(si.CONFIGS[3], name="cfg3_one_layer", layers=1)
-    errs = hz.run_fwd_bwd_parity(cfg, n_micro=1)
+def test_cfg3_gpt_h5120_both_layers():
+    """H 5120, 40 heads, MLP 20480, S 2048, B 2, both layers, one micro-batch against the oracle."""
+    errs = hz.run_fwd_bwd_parity(si.CONFIGS[3], n_micro=1)
     _report("cfg3", errs)
+
+
+def test_cfg3_grouped_weight_gradients_equal_one_by_one():
+    """Self-consistency on the GPU at cfg3's full shape (no oracle: it would need minutes): 4
+    micro-batches with the default group of 4, run back to back, against the same 4 with every
+    backward computing its own weight gradients.  The two differ only in the order of fp32
+    additions; the one-by-one path is the one test_cfg3_gpt_h5120_both_layers compares with the
+    oracle."""
+    import torch
+    cfg = si.CONFIGS[3]
+    params = si.make_params(cfg, 0, 0.0)
+    ins = [(hz.to_dev(si.make_activation(cfg, "act_in", mb, 0), cfg.dtype),
+            hz.to_dev(si.make_activation(cfg, "grad_out", mb, 0), cfg.dtype)) for mb in range(4)]
+    results = []
+    for group in (0, 1):
+        with hz.GpuStage(cfg, wgrad_group=group) as g:
+            g.load_params(params)
+            g.bp.bp_stage_zero_grad(g.h)
+            outs = []
+            for mb in range(4):
+                z = g.forward(0, mb, ins[mb][0])
+                outs.append((z, g.backward(0, mb, ins[mb][1])))
+            torch.cuda.synchronize()
+            grads = {(l, n): g.grad(0, l, n) for l in range(cfg.layers) for n in si.PARAM_NAMES}
+            results.append((outs, grads))
+        print(f"cfg3 group={group} done", flush=True)
+    (outs_g, grads_g), (outs_1, grads_1) = results
+    for mb in range(4):                       # the data path does not depend on the grouping at all
+        assert torch.equal(outs_g[mb][0], outs_1[mb][0]) and torch.equal(outs_g[mb][1], outs_1[mb][1]), mb
+    worst = max(hz.rel_err(grads_g[k], grads_1[k]) for k in grads_g)
+    print("cfg3 grouped vs one-by-one worst rel err", f"{worst:.2e}", flush=True)
+    assert worst <= 1e-4, worst
+
+
+@functools.lru_cache(maxsize=2)
+def _wgrad_family(T, wide, narrow):
+    """Seeded base operands of one config's weight-gradient GEMMs, generated once: X0 [T, narrow]
+    and Y0 [T, wide], N(0,1) rounded to bf16."""
+    x0 = si.round_to(si.normal(si.stream_key(0, "wgx", T, narrow), (T, narrow), 1.0), "bf16")
+    y0 = si.round_to(si.normal(si.stream_key(0, "wgy", T, wide), (T, wide), 1.0), "bf16")
+    return x0, y0
+
+
+def _segment(base, i):
+    """Micro-batch i of a group: the base tensor with its tokens rotated (and its sign flipped for
+    odd i), so that the segments differ and a dropped or repeated segment changes the sum."""
+    a = np.roll(base, 37 * i, axis=0)
+    return -a if i & 1 else a
+
+
+@pytest.mark.parametrize("M,N,T,n", [
+    # cfg1 (T 2048, groups of 8): dW2, dW1, dWqkv, dWo as bench.py's step computes them
+    (8192, 2048, 2048, 8), (2048, 8192, 2048, 8), (2048, 6144, 2048, 8), (2048, 2048, 2048, 8),
+    # cfg3 (T 4096, groups of 4)
+    (20480, 5120, 4096, 4), (5120, 20480, 4096, 4), (5120, 15360, 4096, 4), (5120, 5120, 4096, 4),
+])
+def test_grouped_weight_gradient_gemm_at_bench_shapes(M, N, T, n):
+    """bp_op_wgrad_group at the exact shapes and group sizes of the timed cfg1 / cfg3 steps, with a
+    workspace as the stage passes one: rows and columns of dW sampled so that every 256 x 256
+    output tile (whole tiles and the K-sliced ones of a partly filled last round alike) is crossed,
+    each compared with the oracle's linear_wgrad on the same operands."""
+    import torch
+    import paper_2410_19367_amd as bp
+    wide, narrow = (20480, 5120) if T == 4096 else (8192, 2048)
+    x0, y0 = _wgrad_family(T, wide, narrow)
+    src_x = (y0 if M > narrow else x0)[:, :M]
+    src_y = (x0 if M > narrow else y0)[:, :N]
+    xs = [np.ascontiguousarray(_segment(src_x, i)) for i in range(n)]
+    ys = [np.ascontiguousarray(_segment(src_y, i + 1)) for i in range(n)]
+    rng = np.random.default_rng(M * 31 + N)
+    rows = sorted({min(M - 1, t * 256 + int(o)) for t in range(M // 256) for o in (0, 255, rng.integers(1, 255))})
+    cols = sorted({min(N - 1, t * 256 + int(o)) for t in range(N // 256) for o in (0, 255, rng.integers(1, 255))})
+    w0 = si.normal(si.stream_key(0, "wg0", M, N), (len(rows) + len(cols), max(M, N)), 3.0).astype(np.float32)
+    xcat = np.concatenate(xs).astype(np.float64)
+    ycat = np.concatenate(ys).astype(np.float64)
+    ref_rows, _ = O.linear_wgrad(xcat[:, rows], ycat)          # [len(rows), N]
+    ref_cols, _ = O.linear_wgrad(xcat, ycat[:, cols])          # [M, len(cols)]
+    xd = [hz.to_dev(x, "bf16") for x in xs]
+    yd = [hz.to_dev(y, "bf16") for y in ys]
+    wd = torch.zeros((M, N), device="cuda")
+    # previous accumulator contents on the sampled rows / columns (the call adds to them)
+    r_idx = torch.tensor(rows, device="cuda"); c_idx = torch.tensor(cols, device="cuda")
+    wd[r_idx] = torch.from_numpy(np.ascontiguousarray(w0[:len(rows), :N])).cuda()
+    wd[:, c_idx] = torch.from_numpy(np.ascontiguousarray(w0[len(rows):, :M].T)).cuda()
+    before_rows = wd[r_idx].cpu().numpy().astype(np.float64)
+    before_cols = wd[:, c_idx].cpu().numpy().astype(np.float64)
+    ws = torch.empty(min(4 * M * N, 64 << 20), device="cuda")
+    bp.bp_op_wgrad_group(bp.BP_BF16, M, N, T, xd, yd, wd, 0, ws, ws.numel())
+    torch.cuda.synchronize()
+    err_r = hz.rel_err(wd[r_idx].cpu().numpy(), before_rows + ref_rows)
+    err_c = hz.rel_err(wd[:, c_idx].cpu().numpy(), before_cols + ref_cols)
+    print(f"wgrad group {M}x{N} T={T} n={n}: rows {err_r:.2e} cols {err_c:.2e}", flush=True)
+    assert err_r <= 2e-3 and err_c <= 2e-3, (err_r, err_c)
 
 
 def test_cfg4_v_schedule_full():
