@@ -15,6 +15,7 @@
 // split-K and multi-segment contractions.  Two LDS stages each: slice k+1 lands while slice k
 // feeds the MFMAs, one barrier per slice.
 #include <cstdlib>
+#include <type_traits>
 
 #include "bp_kernels.h"
 #include "bp_device.h"
@@ -246,35 +247,44 @@ template <int BKT> __device__ __forceinline__ int kmaj_off(int row, int c) {
     return row * (BKT * 2) + ((c ^ kmaj_swz<BKT>(row)) << 4);
 }
 
-__device__ __forceinline__ void dma16(const void* gptr, char* lds_wave_base) {
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
-                                     (void __attribute__((address_space(3)))*)lds_wave_base, 16, 0, 0);
+// One wave instruction moves 64 x 16 bytes from global memory straight into 1 KiB of consecutive LDS.
+// The global address is a buffer descriptor (wave-uniform tile origin) plus a per-lane 32-bit byte
+// offset plus a wave-uniform byte offset (the K slice), so issuing a load costs no vector ALU work.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
+    // raw buffer, stride 0, no bounds clamp below 4 GiB - 1; dword 3 as for untyped 32-bit data on gfx9
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)0xffffffffu, 0x00020000);
+}
+__device__ __forceinline__ void dma16(rsrc_t rsrc, uint32_t lane_off, uint32_t slice_off, char* lds_wave_base) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void __attribute__((address_space(3)))*)lds_wave_base, 16,
+                                             (int)lane_off, (int)slice_off, 0, 0);
 }
 
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 #define BP_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 15) | (((N) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-// Per-lane element offsets (relative to the slice base) of the chunks this lane fetches.
+// Per-lane byte offsets (relative to the slice base) of the chunks this lane fetches: 32 bits, so
+// that the load takes the wave-uniform slice base from scalar registers plus this one vector register.
 template <int R, int BKT, int NW, bool RMAJOR>
 struct DmaPlan {
     static constexpr int NI = R * BKT / 512 / NW;   // wave instructions per wave per slice
-    int goff[NI];                                   // element offset from the slice base
+    uint32_t boff[NI];                              // byte offset from the slice base
     __device__ __forceinline__ void init(int wave, int lane, int ld) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int P = (wave + NW * i) * 64 + lane;          // 16-byte position in the tile
             if (RMAJOR) {
                 const int krow = P / (R / 8), p = P % (R / 8);
-                goff[i] = krow * ld + ((p ^ rmajor_swz<R>(krow)) << 3);
+                boff[i] = 2u * (uint32_t)(krow * ld + ((p ^ rmajor_swz<R>(krow)) << 3));
             } else {
                 const int row = P / (BKT / 8), p = P % (BKT / 8);
-                goff[i] = row * ld + ((p ^ kmaj_swz<BKT>(row)) << 3);
+                boff[i] = 2u * (uint32_t)(row * ld + ((p ^ kmaj_swz<BKT>(row)) << 3));
             }
         }
     }
-    __device__ __forceinline__ void issue(const bf16_t* slice_base, char* lds_tile, int wave) const {
+    __device__ __forceinline__ void issue(rsrc_t tile, uint32_t slice_off, char* lds_tile, int wave) const {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) dma16(slice_base + goff[i], lds_tile + (wave + NW * i) * 1024);
+        for (int i = 0; i < NI; ++i) dma16(tile, boff[i], slice_off, lds_tile + (wave + NW * i) * 1024);
     }
 };
 
@@ -318,6 +328,27 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
     tn = (t % per_group) / gsize;
 }
 
+// Issue-order groups for one k16 step of NMFMA MFMAs.  Inside a slice (NLOAD == 0) the step's NREAD
+// LDS reads are spread evenly over all its MFMAs, so the LDS sees a steady stream instead of bursts
+// from every wave at once.  At a slice boundary the reads go out in the first half of the step and
+// the NLOAD direct-to-LDS loads in the second (those write LDS, so they cannot be ordered in front
+// of a read that precedes them in the program).
+constexpr int ceil_div(int a, int b) { return (a + b - 1) / b; }
+template <int R, int NMFMA, int NREAD, int NLOAD>
+struct SchedRounds {
+    static __device__ __forceinline__ void apply() {
+        constexpr int RR = NLOAD ? (NMFMA / 2 > 0 ? NMFMA / 2 : 1) : NMFMA;      // rounds that carry reads
+        constexpr int reads = R >= RR ? 0 : ceil_div((R + 1) * NREAD, RR) - ceil_div(R * NREAD, RR);
+        constexpr int LR = NMFMA - RR > 0 ? NMFMA - RR : 1;                      // rounds that carry loads
+        constexpr int L = NLOAD ? R - (NMFMA - LR) : -1;
+        constexpr int loads = L < 0 ? 0 : ceil_div((L + 1) * NLOAD, LR) - ceil_div(L * NLOAD, LR);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // 1 MFMA
+        if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);   // DS reads
+        if constexpr (loads > 0) __builtin_amdgcn_sched_group_barrier(0x010, loads, 0);   // VMEM
+        if constexpr (R + 1 < NMFMA) SchedRounds<R + 1, NMFMA, NREAD, NLOAD>::apply();
+    }
+};
+
 template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n, int splits,
                                                                int n_full) {
@@ -345,33 +376,40 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
 
     // The contraction runs over g.nseg operand pairs of g.K each; this block owns steps
     // [k_first, k_first + nk) of the concatenation.  (seg, kl) is the position of the next slice
-    // to request and (a_next, b_next) its tile origin.
+    // to request.
     const int nk_seg = g.K / BKT;
     const int nk_all = nk_seg * g.nseg;
     // K slices of a split tile differ by at most one step: the first nk_all % splits get one more
     const int nk = nk_all / eff_splits + (sp < nk_all % eff_splits ? 1 : 0);
     const int k_first = sp * (nk_all / eff_splits) + min(sp, nk_all % eff_splits);
-    const size_t a_step = A_RMAJOR ? (size_t)BKT * g.lda : BKT;
-    const size_t b_step = B_RMAJOR ? (size_t)BKT * g.ldb : BKT;
+    // byte step of one K slice inside a segment
+    const uint32_t a_step = 2u * (uint32_t)(A_RMAJOR ? BKT * g.lda : BKT);
+    const uint32_t b_step = 2u * (uint32_t)(B_RMAJOR ? BKT * g.ldb : BKT);
     auto a_origin = [&](int sgm) {
         const bf16_t* A = (const bf16_t*)(sgm == 0 ? g.A : g.A_more[sgm - 1]);
-        return A_RMAJOR ? A + m0 : A + (size_t)m0 * g.lda;
+        return make_rsrc(A_RMAJOR ? A + m0 : A + (size_t)m0 * g.lda);
     };
     auto b_origin = [&](int sgm) {
         const bf16_t* Bp = (const bf16_t*)(sgm == 0 ? g.B : g.B_more[sgm - 1]);
-        return B_RMAJOR ? Bp + n0 : Bp + (size_t)n0 * g.ldb;
+        return make_rsrc(B_RMAJOR ? Bp + n0 : Bp + (size_t)n0 * g.ldb);
     };
+    // the next slice to request: segment, slice inside it, tile origins of that segment, byte offsets
     int seg = k_first / nk_seg, kl = k_first % nk_seg;
-    const bf16_t* a_next = a_origin(seg) + kl * a_step;
-    const bf16_t* b_next = b_origin(seg) + kl * b_step;
+    rsrc_t a_tile = a_origin(seg), b_tile = b_origin(seg);
+    uint32_t a_off = kl * a_step, b_off = kl * b_step;
+    int issued = 0;                                     // slices requested so far
+    // move on to the next slice, unless the last one has just been requested: then stay on it
     auto advance = [&]() {
-        a_next += a_step;
-        b_next += b_step;
-        if (++kl == nk_seg && seg + 1 < g.nseg) {
+        ++issued;
+        if (issued >= nk) return;
+        a_off += a_step;
+        b_off += b_step;
+        if (++kl == nk_seg) {
             kl = 0;
             ++seg;
-            a_next = a_origin(seg);
-            b_next = b_origin(seg);
+            a_tile = a_origin(seg);
+            b_tile = b_origin(seg);
+            a_off = b_off = 0;
         }
     };
 
@@ -391,15 +429,19 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
 
     constexpr int KK = BKT / 16;
     static_assert(KK >= 2 && KK % 2 == 0, "a K slice is an even number of k16 steps");
+    static_assert(NS >= 2 && NS <= 5, "2 to 5 LDS stages");
     static_assert((NS - 2) * LPT < 64, "outstanding loads must fit the vmcnt field");
     constexpr int NREAD = (TM * (A_RMAJOR ? 2 : 1) + TN * (B_RMAJOR ? 2 : 1));   // LDS reads per k16 step
     bf16x8 fa[2][TM], fb[2][TN];
+    // program order = issue order of the reads: the fragments the step's first MFMAs need (A row
+    // block 0 and every B column block) before the other A row blocks
     auto read_step = [&](const char* sa, int kk, int buf) {
         const char* sb = sa + A_BYTES;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[buf][i] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 32, kk, lane);
+        fa[buf][0] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM), kk, lane);
 #pragma unroll
         for (int j = 0; j < TN; ++j) fb[buf][j] = read_frag2<BN, BKT, B_RMAJOR>(sb, wn * (BN / WN) + j * 32, kk, lane);
+#pragma unroll
+        for (int i = 1; i < TM; ++i) fa[buf][i] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 32, kk, lane);
     };
     auto mfma_step = [&](int buf) {
 #pragma unroll
@@ -408,13 +450,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
     };
-    auto interleave = [&]() {        // issue order: one LDS read between MFMAs until the reads are out
-#pragma unroll
-        for (int r = 0; r < NREAD; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 DS read
-        }
-    };
+    // Issue order inside a k16 step, pinned completely (an MFMA left out of the groups could drift
+    // across the slice boundary): the LDS reads of the next step spread over the first MFMAs.  At a
+    // slice boundary the MFMAs of the slice's last k16 step also carry the direct-to-LDS loads of the
+    // slice NS ahead.
+    constexpr int NMFMA = TM * TN;
+    auto interleave = [&]() { SchedRounds<0, NMFMA, NREAD, 0>::apply(); };
+    auto interleave_boundary = [&]() { SchedRounds<0, NMFMA, NREAD, LPT>::apply(); };
     // wait until at most `n` of the most recently requested slices are still on their way
     auto wait_slices = [&](int n) {
         if (NS > 4 && n >= 3) { BP_WAIT_VMCNT(3 * LPT); }
@@ -422,58 +464,78 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
         else if (NS > 2 && n == 1) { BP_WAIT_VMCNT(1 * LPT); }
         else { BP_WAIT_VMCNT(0); }
     };
-    static_assert(NS >= 2 && NS <= 5, "2 to 5 LDS stages");
 
     // NS stages: while slice kt feeds the MFMAs, slices kt+1 .. kt+NS-1 are landing or have landed.
     // The barrier between slices sits in front of the *last* k16 step of a slice, whose fragments are
     // already in registers.  Past the barrier the first fragments of the next slice are requested and
-    // the loads of slice kt+NS are issued into the stage just freed, and the MFMAs of that last step
-    // cover their latency, so no wave starts a slice with an empty matrix pipe.
+    // the loads of slice kt+NS are issued into the stage just freed, in between the MFMAs of that last
+    // step, so no wave starts a slice with an empty matrix pipe.
+    // The loop body has no branches (the compiler interleaves and counts outstanding reads exactly
+    // only inside one basic block): once every slice has been requested the body keeps requesting
+    // the last one again (into stages nobody reads any more) and past the last slice it reads
+    // fragments nobody uses; the change from one contraction segment to the next happens between
+    // runs of the loop.
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) {
         if (s < nk) {
-            pa.issue(a_next, smem + s * STAGE, wave);
-            pb.issue(b_next, smem + s * STAGE + A_BYTES, wave);
+            pa.issue(a_tile, a_off, smem + s * STAGE, wave);
+            pb.issue(b_tile, b_off, smem + s * STAGE + A_BYTES, wave);
             advance();
         }
     }
     wait_slices(min(nk, NS - 1) - 1);                   // slice 0 has landed
     __syncthreads();
     if (NS - 1 < nk) {
-        pa.issue(a_next, smem + (NS - 1) * STAGE, wave);
-        pb.issue(b_next, smem + (NS - 1) * STAGE + A_BYTES, wave);
+        pa.issue(a_tile, a_off, smem + (NS - 1) * STAGE, wave);
+        pb.issue(b_tile, b_off, smem + (NS - 1) * STAGE + A_BYTES, wave);
         advance();
     }
     read_step(smem, 0, 0);
     int cur = 0;                                        // stage of slice kt
-    for (int kt = 0; kt < nk; ++kt) {
-        const char* sa = smem + cur * STAGE;
+    int kt = 0;
+    while (kt < nk) {
+        // a run of the loop below never takes the requests across the end of a segment
+        const int run = issued < nk ? min(nk - kt, nk_seg - kl) : nk - kt;
+        for (int it = 0; it < run; ++it) {
+            const char* sa = smem + cur * STAGE;
 #pragma unroll
-        for (int kk = 0; kk + 1 < KK; ++kk) {
-            read_step(sa, kk + 1, (kk + 1) & 1);
-            mfma_step(kk & 1);
-            interleave();
-        }
-        if (kt + 1 < nk) {
+            for (int kk = 0; kk + 1 < KK; ++kk) {
+                read_step(sa, kk + 1, (kk + 1) & 1);
+                mfma_step(kk & 1);
+                interleave();
+            }
             // every LDS read of slice kt has returned (the last ones feed the MFMAs below) and this
             // wave's part of slice kt+1 has landed: the barrier publishes that slice and frees the
             // stage of slice kt
+            __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0)
-            wait_slices(min(nk, kt + NS) - (kt + 2));
+            BP_WAIT_VMCNT((NS - 2) * LPT);
             __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
             const int nxt = cur + 1 == NS ? 0 : cur + 1;
             read_step(smem + nxt * STAGE, 0, 0);
-            if (kt + NS < nk) {
-                char* st = smem + cur * STAGE;
-                pa.issue(a_next, st, wave);
-                pb.issue(b_next, st + A_BYTES, wave);
-                advance();
-            }
+            char* st = smem + cur * STAGE;
+            pa.issue(a_tile, a_off, st, wave);
+            pb.issue(b_tile, b_off, st + A_BYTES, wave);
+            // (no branch) the offsets stop moving once the last slice has been requested
+            ++issued;
+            a_off += issued < nk ? a_step : 0u;
+            b_off += issued < nk ? b_step : 0u;
+            mfma_step((KK - 1) & 1);
+            interleave_boundary();
             cur = nxt;
         }
-        mfma_step((KK - 1) & 1);
-        if (kt + 1 < nk) interleave();
+        kt += run;
+        kl += run;
+        if (issued < nk && kl == nk_seg) {
+            kl = 0;
+            ++seg;
+            a_tile = a_origin(seg);
+            b_tile = b_origin(seg);
+            a_off = b_off = 0;
+        }
     }
+    BP_WAIT_VMCNT(0);                                   // the repeated requests too have landed
 
     // ---- epilogue through LDS.  The accumulators hold one column and 16 scattered rows per
     // lane; writing them out directly costs one narrow store instruction per element.  Each
