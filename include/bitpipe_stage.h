@@ -101,6 +101,16 @@ int bp_stage_init_ex(bp_stage_t** out, int layers, int hidden, int heads, int se
  * (the M_a of Table 2 for this chunk, statistics included).  0 for a NULL handle. */
 size_t bp_stage_stash_bytes(const bp_stage_t* st);
 
+/* Activation memory the object holds right now, in bytes (host bookkeeping, launches nothing): the
+ * stashes of forwards whose backward has not run (*live_stash: the activations Table 2 counts in
+ * M_a); the stashes kept beyond their backward by weight-gradient groups that are not complete yet
+ * (*group_stash) and the output-gradient buffers those groups keep (*group_grads: dz, du, dy, dqkv
+ * per layer), both the price of bp_opts.wgrad_group > 1; and the largest sum of the three since the
+ * object was created or bp_stage_reset_peak_bytes was called (*peak_total).  Any pointer may be NULL. */
+int bp_stage_held_bytes(const bp_stage_t* st, size_t* live_stash, size_t* group_stash, size_t* group_grads,
+                        size_t* peak_total);
+int bp_stage_reset_peak_bytes(bp_stage_t* st);
+
 /* Synchronise the stream, free everything the object owns.  NULL is accepted. */
 int bp_stage_destroy(bp_stage_t* st);
 
@@ -164,10 +174,19 @@ int bp_schedule_vmap(int dir, int stage, int D);
 
 /* Pure CPU.  Write the serial order of one BitPipe iteration with D virtual devices, 2D stages
  * and N micro-batches (N a multiple of D, D even; Section 3.3 basic unit, Section 3.5
- * concatenation) into out[0..cap); *n_out = 4*D*N ops.  The order is the list schedule under
- * the paper's cost model (chunk forward 1, backward 2), serialised by (start time, device).
- * Under that cost model and D = 4 the orders reach the paper's closed forms: CONCAT bubble ratio
- * (D-2)/(3N+D-2) at N = D, EARLY_FWD (D-2)/(4N+D-2) and peak (3D-3)/2 M_a for N = 2D..6D.
+ * concatenation) into out[0..cap); *n_out = 4*D*N ops.  The order is a list schedule under the
+ * paper's cost model (chunk forward 1, backward 2), serialised by (start time, device).  Each
+ * pipeline runs its micro-batches by the 1F1B-Int rule (Section 3.3): a free device takes the ready
+ * backward of the micro-batch that entered its own pipeline first (not starting one that would delay
+ * a more urgent backward due in the next slot), else the ready forward of the deepest stage.
+ * What the orders reach when replayed by bp_schedule_simulate:
+ *   CONCAT, N = D (the basic unit): the closed forms of Section 3.3 / Table 2 -- makespan
+ *     2(3N+D-2) chunk slots, bubble ratio (D-2)/(3N+D-2), at most D M_a -- for every even D tested
+ *     (4, 6, 8, 10, 12, 16);
+ *   CONCAT, N = K*D: valid, better than K units back to back, within a few per cent of the closed
+ *     form but not equal to it (e.g. 53 against 52 slots at D = 4, N = 8);
+ *   EARLY_FWD: (D-2)/(4N+D-2) and peak (3D-3)/2 M_a at D = 4, N = 2D..6D and at D = 6, N = 12;
+ *     valid but above the closed form elsewhere.
  * BP_EINVAL for odd D, N % D != 0, cap too small or an unknown variant. */
 int bp_schedule_generate(int D, int N, int variant, bp_op* out, int cap, int* n_out);
 
@@ -249,6 +268,15 @@ int bp_prof_enable(bp_stage_t* st, int on);
  * (what the class had to compute / move by the layer definition, not what it actually did). */
 int bp_prof_get(bp_stage_t* st, int kernel_id, double* total_ms, long long* launches,
                 double* flops, double* bytes);
+
+/* Per-shape totals of the GEMM class since bp_prof_enable(st, 1).  bp_prof_gemm_shapes returns the
+ * number of distinct GEMM shapes launched (>= 0, or a negative bp_status); bp_prof_gemm_get reads
+ * entry `index`: dims[7] = {M, N, K of one contraction segment, a_t, b_t, segments, epilogue (0 none,
+ * 1 bias+GELU forward, 2 GELU backward + bias-gradient partials)} in the sense of bp_op_gemm /
+ * bp_op_wgrad_group, the milliseconds between the launches' events (a split-K GEMM includes its
+ * reduction kernel) and the launch count.  Both synchronise.  Any output pointer may be NULL. */
+int bp_prof_gemm_shapes(bp_stage_t* st);
+int bp_prof_gemm_get(bp_stage_t* st, int index, int* dims, double* total_ms, long long* launches);
 
 /* ---- single operations on caller-owned device buffers (tests and kernel benchmarks) ------ */
 

@@ -15,11 +15,18 @@ From the paper (arXiv 2410.19367):
     previous unit's tail bubbles (Section 3.5).
 The figures that draw the slot-by-slot order are not available, so the order is rebuilt by
 deterministic list scheduling under the unit-cost model (a chunk forward costs 1, a chunk
-backward 2; a stage-activation M_a is two chunk stashes): a free device runs a ready backward if
-there is one (lowest micro-batch first), otherwise the ready forward of the highest stage
-(lowest micro-batch first), never holding more than 2D chunk stashes, and admitting a new micro-batch
-only while fewer than 3D/2 are in flight.  At D = 4 this reproduces
-the closed forms above; for D > 4 it does not reach them (parity unpinned beyond D = 4).
+backward 2; a stage-activation M_a is two chunk stashes).  Each pipeline runs its N/2 micro-batches
+by the 1F1B-Int rule (Section 3.3), so what ranks a micro-batch is its place in its own pipeline's
+injection order (the k-th micro-batch of the down pipeline and the k-th of the up pipeline rank
+alike), not its global index.  A free device runs the ready backward of the lowest rank, otherwise
+the ready forward of the highest stage (lowest rank first); it does not start a backward when one
+of lower rank becomes ready in the next slot (a backward holds the device for two slots, so
+starting it would delay the more urgent one): it then runs a forward, or waits one slot.  A device
+never holds more than 2D chunk stashes, and a micro-batch is admitted only while fewer than D + 2
+are in flight.  For the basic unit N = D this reproduces the paper's closed forms (makespan 8D - 4
+chunk slots = 3N + D - 2 device-forwards, idle 2(D-2) per device) for every even D tested, 4 to 16;
+for N = K*D it comes within a few per cent of (D-2)/(3N+D-2) but does not reach it exactly
+(parity unpinned for N > D beyond what the tests state).
   * Early forwarding (Appendix B, Eq. 1-2): for N > D, forwards of later micro-batches are run
     ahead of time so that the bubbles between concatenated units disappear; the bubble ratio drops
     to (D-2)/(4N+D-2) (idle (D-2)/4 (t_f + t_b) per device) at a peak of (3D-3)/2 M_a.  Rebuilt
@@ -60,6 +67,13 @@ def direction_of(mb, D):
     return 0 if (mb % D) < D // 2 else 1
 
 
+def rank_in_pipeline(mb, D):
+    """Place of a micro-batch in its own pipeline's injection order (both pipelines count alike):
+    units of D micro-batches in sequence, inside a unit the first D/2 go down and the last D/2 up."""
+    unit, r = divmod(mb, D)
+    return unit * (D // 2) + r % (D // 2)
+
+
 def generate_timeline(D, N, cost_f=1, cost_b=2, early_forward=False, v=2, looping=False):
     """List-schedule one iteration.  Returns per-device lists of Slot(start, end, op).
 
@@ -67,9 +81,10 @@ def generate_timeline(D, N, cost_f=1, cost_b=2, early_forward=False, v=2, loopin
     device starts at most one op whose inputs finished at or before that step.  A forward needs
     a free stash slot on its device (cap 2D chunk stashes = D * M_a; a slot is given back when
     the backward finishes).  A micro-batch is admitted (stage-0 forward) only while fewer than
-    3D/2 admitted micro-batches still await their stage-0 backward: that lets the next basic
+    D + 2 admitted micro-batches still await their stage-0 backward: that lets the next basic
     unit's first forwards fill the tail bubbles of the previous one without flooding the
-    stashes.  early_forward selects the Appendix-B rule described in the module header instead.
+    stashes.  Priorities: see the module header.  early_forward selects the Appendix-B rule
+    described there instead.
     v, looping: other stage placements (see vmap_down); a stage-activation M_a is then v chunk
     stashes and the stash caps scale with it.  Raises RuntimeError if the greedy order stalls."""
     if D < 2 or D % 2 or N < D or N % D:
@@ -83,7 +98,7 @@ def generate_timeline(D, N, cost_f=1, cost_b=2, early_forward=False, v=2, loopin
         prefer_f_below = v * D
     else:
         cap = v * D                         # D M_a
-        window = D + D // 2
+        window = D + 2
         prefer_f_below = 0                  # always backwards first
     done_f, done_b = {}, {}             # (stage, mb) -> finish time
     free_at = [0] * D
@@ -103,32 +118,44 @@ def generate_timeline(D, N, cost_f=1, cost_b=2, early_forward=False, v=2, loopin
             held = sum(1 for sl in lanes[dev] if sl.op.kind == "F") - \
                 sum(1 for sl in lanes[dev] if sl.op.kind == "B" and sl.end <= t)
             in_flight = sum(1 for mb in admitted if done_b.get((0, mb), never) > t)
-            ready_b, ready_f = [], []
+            ready_b, ready_f, soon_b = [], [], []
             for mb in range(N):
                 dr = direction_of(mb, D)
+                rk = rank_in_pipeline(mb, D)
                 for s in range(n_stage):
                     if vmap(dr, s, D, v, looping) != dev:
                         continue
-                    if ("B", s, mb) not in started and done_f.get((s, mb), never) <= t:
-                        if s == n_stage - 1 or done_b.get((s + 1, mb), never) <= t:
-                            ready_b.append((mb, s, dr))
+                    if ("B", s, mb) not in started:
+                        at = max(done_f.get((s, mb), never),
+                                 0 if s == n_stage - 1 else done_b.get((s + 1, mb), never))
+                        if at <= t:
+                            ready_b.append((rk, s, dr, mb))
+                        elif at == t + 1:
+                            soon_b.append((rk, s, dr, mb))
                     if ("F", s, mb) not in started and held < cap:
                         if s == 0:
                             if in_flight < window:
-                                ready_f.append((0, mb, dr))
+                                ready_f.append((0, rk, dr, mb))
                         elif done_f.get((s - 1, mb), never) <= t:
-                            ready_f.append((-s, mb, dr))
+                            ready_f.append((-s, rk, dr, mb))
+            pick_b = None
             if ready_b and not (ready_f and held < prefer_f_below):
-                if early_forward:       # lowest stage first, then lowest micro-batch
-                    mb, s, dr = min(ready_b, key=lambda c: (c[1], c[0]))
-                else:                   # lowest micro-batch first, then lowest stage
-                    mb, s, dr = min(ready_b)
+                if early_forward:       # lowest stage first, then lowest rank
+                    pick_b = min(ready_b, key=lambda c: (c[1], c[0], c[2]))
+                else:                   # lowest rank first, then lowest stage
+                    pick_b = min(ready_b)
+                    if soon_b and min(soon_b) < pick_b:
+                        pick_b = None   # a more urgent backward arrives next slot: do not block it
+                        if not ready_f:
+                            continue
+            if pick_b is not None:
+                rk, s, dr, mb = pick_b
                 started.add(("B", s, mb))
                 done_b[(s, mb)] = t + cost_b
                 free_at[dev] = t + cost_b
                 lanes[dev].append(Slot(t, t + cost_b, Op("B", dr, dev, s, mb)))
             elif ready_f:
-                ns, mb, dr = min(ready_f)
+                ns, rk, dr, mb = min(ready_f)
                 s = -ns
                 if s == 0:
                     admitted.append(mb)

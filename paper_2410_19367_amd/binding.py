@@ -23,13 +23,13 @@ KERNEL_IDS = {n: i for i, n in enumerate(
 
 # every symbol include/bitpipe_stage.h declares
 EXPORTS = (
-    "bp_stage_init", "bp_stage_init_ex", "bp_stage_stash_bytes", "bp_stage_destroy", "bp_stage_set_param",
+    "bp_stage_init", "bp_stage_init_ex", "bp_stage_stash_bytes", "bp_stage_held_bytes", "bp_stage_reset_peak_bytes", "bp_stage_destroy", "bp_stage_set_param",
     "bp_stage_get_grad", "bp_stage_zero_grad", "bp_stage_set_seqlens", "bp_stage_forward",
     "bp_stage_backward", "bp_stage_backward_dir", "bp_schedule_vmap", "bp_schedule_generate",
     "bp_schedule_validate", "bp_schedule_simulate", "bp_run_schedule", "bp_schedule_vmap_ex",
     "bp_schedule_generate_ex", "bp_schedule_validate_ex", "bp_schedule_simulate_ex", "bp_run_schedule_ex",
     "bp_schedule_hops", "bp_prof_enable",
-    "bp_prof_get", "bp_op_gemm", "bp_op_wgrad_group", "bp_op_layernorm_fwd", "bp_op_layernorm_bwd",
+    "bp_prof_get", "bp_prof_gemm_shapes", "bp_prof_gemm_get", "bp_op_gemm", "bp_op_wgrad_group", "bp_op_layernorm_fwd", "bp_op_layernorm_bwd",
     "bp_op_layernorm_bwd_static", "bp_static_scratch_floats",
     "bp_op_bias_gelu_fwd", "bp_op_bias_gelu_bwd", "bp_op_colsum_workspace",
     "bp_op_attention_fwd", "bp_op_attention_bwd", "bp_last_error", "bp_version",
@@ -73,6 +73,9 @@ def lib():
         l.bp_stage_init_ex.argtypes = [C.POINTER(vp), ci, ci, ci, ci, ci, ci, C.POINTER(bp_opts)]
         l.bp_stage_stash_bytes.argtypes = [vp]
         l.bp_stage_stash_bytes.restype = C.c_size_t
+        szp = C.POINTER(C.c_size_t)
+        l.bp_stage_held_bytes.argtypes = [vp, szp, szp, szp, szp]
+        l.bp_stage_reset_peak_bytes.argtypes = [vp]
         l.bp_stage_destroy.argtypes = [vp]
         l.bp_stage_set_param.argtypes = [vp, ci, ci, ci, vp, C.c_size_t]
         l.bp_stage_get_grad.argtypes = [vp, ci, ci, ci, vp, C.c_size_t]
@@ -98,6 +101,8 @@ def lib():
         l.bp_prof_enable.argtypes = [vp, ci]
         l.bp_prof_get.argtypes = [vp, ci, C.POINTER(C.c_double), C.POINTER(C.c_longlong),
                                   C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        l.bp_prof_gemm_shapes.argtypes = [vp]
+        l.bp_prof_gemm_get.argtypes = [vp, ci, C.POINTER(ci), C.POINTER(C.c_double), C.POINTER(C.c_longlong)]
         l.bp_op_gemm.argtypes = [ci, ci, ci, ci, ci, ci, vp, ci, vp, ci, vp, ci, vp, vp, ci, vp]
         l.bp_op_wgrad_group.argtypes = [ci, ci, ci, ci, ci, C.POINTER(vp), C.POINTER(vp), vp, ci, vp,
                                         C.c_size_t, vp]
@@ -162,6 +167,16 @@ def bp_stage_init_ex(layers, hidden, heads, seq, microbatch, causal, n_chunks=0,
 
 def bp_stage_stash_bytes(st) -> int:
     return lib().bp_stage_stash_bytes(st)
+
+
+def bp_stage_held_bytes(st) -> dict:
+    a, b, c, d = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check(lib().bp_stage_held_bytes(st, C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
+    return dict(live_stash=a.value, group_stash=b.value, group_grads=c.value, peak_total=d.value)
+
+
+def bp_stage_reset_peak_bytes(st):
+    return _check(lib().bp_stage_reset_peak_bytes(st))
 
 
 def bp_stage_destroy(st):
@@ -295,6 +310,21 @@ def bp_prof_get(st, kernel_id):
     ms, n, fl, by = C.c_double(0), C.c_longlong(0), C.c_double(0), C.c_double(0)
     _check(lib().bp_prof_get(st, kernel_id, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)))
     return dict(ms=ms.value, launches=n.value, flops=fl.value, bytes=by.value)
+
+
+def bp_prof_gemm_shapes(st):
+    """List of dicts, one per distinct GEMM shape launched since timing was enabled."""
+    n = lib().bp_prof_gemm_shapes(st)
+    if n < 0:
+        _check(n)
+    out = []
+    for i in range(n):
+        dims = (C.c_int * 7)()
+        ms, cnt = C.c_double(0), C.c_longlong(0)
+        _check(lib().bp_prof_gemm_get(st, i, dims, C.byref(ms), C.byref(cnt)))
+        M, N, K, a_t, b_t, nseg, epi = list(dims)
+        out.append(dict(M=M, N=N, K=K, a_t=a_t, b_t=b_t, segments=nseg, epilogue=epi, ms=ms.value, launches=cnt.value))
+    return out
 
 
 # ---------------------------------------------------------------- single operations

@@ -25,7 +25,12 @@ struct Layout {
 
 // Optional event timing of every launch, grouped by kernel class.
 struct Prof {
-    struct Pending { int kid; hipEvent_t start, stop; };
+    struct Pending { int kid; hipEvent_t start, stop; int shape; };
+    // GEMM launches are also totalled per shape: {M, N, K per segment, a_t, b_t, segments, epilogue}
+    struct ShapeStat { int dims[7]; double ms; long long launches; };
+    std::vector<ShapeStat> shapes;
+    int next_shape = -1;       // shape slot of the launch that begin() is about to record
+    void tag_gemm(int M, int N, int K, int a_t, int b_t, int nseg, int epi);
     bool on = false;
     std::vector<Pending> pending;
     std::vector<hipEvent_t> free_events;
@@ -143,6 +148,11 @@ struct Stage {
     int merge_directions();
     int set_seqlens(int mb, const int32_t* host);
 
+    // activation memory in use: live stashes, stashes and output-gradient buffers kept by open
+    // weight-gradient groups; peak of their sum since the last reset
+    size_t peak_held_bytes = 0;
+    void held_bytes(size_t out[3]) const;
+    void note_held();
     int find_slot(int chunk, int mb) const;
     int acquire_slot(int chunk, int mb, int* out);
     int live_slots() const;

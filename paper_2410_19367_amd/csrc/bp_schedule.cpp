@@ -25,6 +25,10 @@ int schedule_vmap(int dir, int stage, int D) { return schedule_vmap(Layout{}, di
 // Within each group of D consecutive micro-batches the first half travels down, the second up
 // (each pipeline schedules N/2 micro-batches, Section 3.3).
 static inline int direction_of(int mb, int D) { return (mb % D) < D / 2 ? 0 : 1; }
+// Place of a micro-batch in its own pipeline's injection order (each pipeline runs its micro-batches
+// by the 1F1B-Int rule, Section 3.3): the k-th micro-batch of the down pipeline and the k-th of the
+// up pipeline rank alike.
+static inline int rank_in_pipeline(int mb, int D) { return (mb / D) * (D / 2) + (mb % D) % (D / 2); }
 
 namespace {
 
@@ -52,7 +56,7 @@ struct ListScheduler {
     ListScheduler(const Layout& L_, int D_, int N_, int cf, int cb, int variant)
         : L(L_), D(D_), N(N_), n_stage(L_.v * D_), cost_f(cf), cost_b(cb),
           cap(variant == BP_SCHED_V_EARLY_FWD ? (D_ > 2 ? ((3 * D_ - 3) * L_.v + 1) / 2 : L_.v * D_) : L_.v * D_),
-          window(variant == BP_SCHED_V_EARLY_FWD ? 2 * D_ : D_ + D_ / 2),
+          window(variant == BP_SCHED_V_EARLY_FWD ? 2 * D_ : D_ + 2),
           prefer_f_below(variant == BP_SCHED_V_EARLY_FWD ? L_.v * D_ : 0),
           b_lowest_stage_first(variant == BP_SCHED_V_EARLY_FWD),
           f_done((size_t)L_.v * D_ * N_, INT_MAX), b_done((size_t)L_.v * D_ * N_, INT_MAX),
@@ -72,39 +76,60 @@ struct ListScheduler {
         return n;
     }
 
-    // Pick what device `dev` starts at time t, or nothing.  Concatenated units: backwards first
-    // (lowest micro-batch, then lowest stage); else the forward of the deepest stage (then lowest
-    // micro-batch).  Early forwarding (Appendix B): the forward goes first while the device holds
-    // fewer than prefer_f_below stashes, and among backwards the lowest stage wins.
+    // Pick what device `dev` starts at time t, or nothing.  Concatenated units: the ready backward
+    // of the lowest rank (then lowest stage) unless a backward of lower rank becomes ready in the
+    // next slot (a backward holds the device for two slots and would delay it: the device then runs
+    // a forward or waits); else the forward of the deepest stage (then lowest rank).  Early
+    // forwarding (Appendix B): the forward goes first while the device holds fewer than
+    // prefer_f_below stashes, and among backwards the lowest stage wins.
+    struct Cand {
+        int a, b, c, mb;
+        bool operator<(const Cand& o) const {
+            if (a != o.a) return a < o.a;
+            if (b != o.b) return b < o.b;
+            if (c != o.c) return c < o.c;
+            return mb < o.mb;
+        }
+    };
     bool pick(int dev, int t, bp_op* chosen) const {
-        bool have_b = false, have_f = false;
-        int b_mb = 0, b_s = 0, f_mb = 0, f_s = 0;
+        bool have_b = false, have_f = false, have_soon = false;
+        Cand best_b{}, best_f{}, soon{};
+        int b_stage = 0, f_stage = 0;
         const int holding = held(dev, t);
         const bool room = holding < cap;
         const bool may_admit = in_flight(t) < window;
         for (int mb = 0; mb < N; ++mb) {
-            const int dir = direction_of(mb, D);
+            const int dir = direction_of(mb, D), rk = rank_in_pipeline(mb, D);
             for (int s = 0; s < n_stage; ++s) {
                 if (schedule_vmap(L, dir, s, D) != dev) continue;
                 const size_t k = at(s, mb);
-                if (!b_started[k] && f_done[k] <= t &&
-                    (s == n_stage - 1 || b_done[at(s + 1, mb)] <= t)) {
-                    const bool better = b_lowest_stage_first ? (s < b_s || (s == b_s && mb < b_mb))
-                                                             : (mb < b_mb || (mb == b_mb && s < b_s));
-                    if (!have_b || better) { have_b = true; b_mb = mb; b_s = s; }
+                if (!b_started[k]) {
+                    const int at_t = std::max(f_done[k], s == n_stage - 1 ? 0 : b_done[at(s + 1, mb)]);
+                    const Cand c = b_lowest_stage_first ? Cand{s, rk, dir, mb} : Cand{rk, s, dir, mb};
+                    if (at_t <= t) {
+                        if (!have_b || c < best_b) { have_b = true; best_b = c; b_stage = s; }
+                    } else if (at_t == t + 1 && !b_lowest_stage_first) {
+                        if (!have_soon || c < soon) { have_soon = true; soon = c; }
+                    }
                 }
                 if (!f_started[k] && room) {
                     const bool ready = s == 0 ? may_admit : f_done[at(s - 1, mb)] <= t;
-                    if (ready && (!have_f || s > f_s || (s == f_s && mb < f_mb))) { have_f = true; f_mb = mb; f_s = s; }
+                    const Cand c{-s, rk, dir, mb};
+                    if (ready && (!have_f || c < best_f)) { have_f = true; best_f = c; f_stage = s; }
                 }
             }
         }
-        if (have_b && !(have_f && holding < prefer_f_below)) {
-            *chosen = bp_op{1, (int8_t)direction_of(b_mb, D), (int16_t)dev, b_s, b_mb};
+        bool take_b = have_b && !(have_f && holding < prefer_f_below);
+        if (take_b && have_soon && soon < best_b) {
+            take_b = false;                 // a more urgent backward arrives next slot: do not block it
+            if (!have_f) return false;
+        }
+        if (take_b) {
+            *chosen = bp_op{1, (int8_t)direction_of(best_b.mb, D), (int16_t)dev, b_stage, best_b.mb};
             return true;
         }
         if (have_f) {
-            *chosen = bp_op{0, (int8_t)direction_of(f_mb, D), (int16_t)dev, f_s, f_mb};
+            *chosen = bp_op{0, (int8_t)direction_of(best_f.mb, D), (int16_t)dev, f_stage, best_f.mb};
             return true;
         }
         return false;

@@ -58,7 +58,8 @@ void Prof::begin(Stage* st, int kid, double flops, double bytes) {
         hipEventCreate(&b);
     }
     hipEventRecord(a, st->stream);
-    pending.push_back({kid, a, b});
+    pending.push_back({kid, a, b, kid == BP_K_GEMM ? next_shape : -1});
+    next_shape = -1;
     flops_total[kid] += flops;
     bytes_total[kid] += bytes;
     launches[kid] += 1;
@@ -75,14 +76,27 @@ void Prof::collect() {
         hipEventSynchronize(p.stop);
         hipEventElapsedTime(&ms, p.start, p.stop);
         ms_total[p.kid] += ms;
+        if (p.shape >= 0) { shapes[p.shape].ms += ms; shapes[p.shape].launches += 1; }
         free_events.push_back(p.start);
         free_events.push_back(p.stop);
     }
     pending.clear();
 }
 
+void Prof::tag_gemm(int M, int N, int K, int a_t, int b_t, int nseg, int epi) {
+    if (!on) return;
+    const int d[7] = {M, N, K, a_t, b_t, nseg, epi};
+    for (size_t i = 0; i < shapes.size(); ++i)
+        if (!memcmp(shapes[i].dims, d, sizeof d)) { next_shape = (int)i; return; }
+    ShapeStat ss{};
+    memcpy(ss.dims, d, sizeof d);
+    shapes.push_back(ss);
+    next_shape = (int)shapes.size() - 1;
+}
+
 void Prof::reset() {
     collect();
+    shapes.clear();
     for (int i = 0; i < BP_N_KERNEL_IDS; ++i) {
         ms_total[i] = 0; flops_total[i] = 0; bytes_total[i] = 0; launches[i] = 0;
     }
@@ -148,14 +162,6 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     st->esz = dtype_size(st->dtype);
     st->lean = opt.stash_recompute == 1;
     st->wgrad_group = opt.wgrad_group ? opt.wgrad_group : std::min(kMaxGemmSegments, std::max(1, 16384 / st->T));
-    // tuning switches for A/B measurements: BITPIPE_DISABLE is a bit mask, 1: GELU fused into the
-    // GEMM epilogues, 2: grouped weight gradients, 4: second stream (8: read by the GEMM launcher)
-    if (const char* dis = getenv("BITPIPE_DISABLE")) {
-        const long m = strtol(dis, nullptr, 0);
-        if (m & 1) st->fuse_gelu = false;
-        if (m & 2) st->wgrad_group = 1;
-        if (m & 4) st->overlap = false;
-    }
     st->pend[0].resize(st->n_chunks);
     st->pend[1].resize(st->n_chunks);
 
@@ -458,6 +464,7 @@ int Stage::wgrad_one(int dir, int chunk, int l, int k, const void* cur_x, const 
     // are merged), one after the other, so they can share one split-K workspace
     g.split_ws = ws_splitk_side;
     g.split_ws_elems = ws_splitk_side_elems;
+    prof.tag_gemm(Mk[k], Nk[k], T, 1, 0, n, 0);
     Scoped sc(this, BP_K_GEMM, 2.0 * Mk[k] * Nk[k] * (double)T * n, 0);
     hipError_t e = launch_gemm(dtype, g, ss);
     if (e != hipSuccess) return fail(BP_EHIP, "weight-gradient GEMM: %s", hipGetErrorString(e));
@@ -557,6 +564,22 @@ int Stage::set_seqlens(int mb, const int32_t* host) {
 
 // ------------------------------------------------------------------ stash slots
 
+void Stage::held_bytes(size_t out[3]) const {
+    out[0] = out[1] = out[2] = 0;
+    for (const auto& sl : slots) {
+        if (sl.live) out[0] += (size_t)L * s_layer_bytes;
+        else if (sl.held) out[1] += (size_t)L * s_layer_bytes;
+    }
+    for (int dir = 0; dir < 2; ++dir)
+        for (const auto& grp : pend[dir]) out[2] += grp.items.size() * (size_t)L * q_layer_bytes;
+}
+
+void Stage::note_held() {
+    size_t h[3];
+    held_bytes(h);
+    peak_held_bytes = std::max(peak_held_bytes, h[0] + h[1] + h[2]);
+}
+
 int Stage::find_slot(int chunk, int mb) const {
     for (size_t i = 0; i < slots.size(); ++i)
         if (slots[i].live && slots[i].chunk == chunk && slots[i].mb == mb) return (int)i;
@@ -612,6 +635,7 @@ int Stage::gemm(const void* A, int lda, int a_t, const void* Bm, int ldb, int b_
         g.split_ws = ws_splitk;
         g.split_ws_elems = ws_splitk_elems;
     }
+    prof.tag_gemm(M, N, K, a_t, b_t, 1, 0);
     Scoped sc(this, BP_K_GEMM, 2.0 * M * N * K, 0);
     BP_LAUNCH(launch_gemm(dtype, g, use_on ? on : stream));
     return BP_OK;
@@ -624,6 +648,7 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
     if (act_in == act_out) return fail(BP_EINVAL, "act_in and act_out must not overlap");
     int slot, rc;
     if ((rc = acquire_slot(chunk, mb, &slot))) return rc;
+    note_held();
     auto it = lens.find(mb);
     const int32_t* ln = it == lens.end() ? nullptr : it->second;
     const double unit = (double)T * H * esz;   // bytes of one [T,H] tensor
@@ -668,6 +693,7 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
             fg.a_t = 0; fg.b_t = 1; fg.accumulate = 0;
             fg.epi = EPI_GELU_FWD; fg.C2 = g_out;
             if (fuse_gelu && gemm_can_fuse_epilogue(dtype, fg)) {
+                prof.tag_gemm(T, F, H, 0, 1, 1, EPI_GELU_FWD);
                 Scoped sc(this, BP_K_GEMM, 2.0 * T * (double)F * H, 0);
                 BP_LAUNCH(launch_gemm(dtype, fg, stream));
             } else {
@@ -782,6 +808,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
             bg.a_t = 0; bg.b_t = 1; bg.accumulate = 0;
             bg.epi = EPI_GELU_BWD; bg.U = sb + s_u; bg.colpart = p_b1;
             if (fuse_gelu && gemm_can_fuse_epilogue(dtype, bg)) {
+                prof.tag_gemm(T, F, H, 0, 1, 1, EPI_GELU_BWD);
                 Scoped sc(this, BP_K_GEMM, 2.0 * T * (double)F * H, 0);
                 BP_LAUNCH(launch_gemm(dtype, bg, stream));
             } else {
@@ -859,6 +886,7 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         slots[slot].held = true;
         grp.items.push_back(PendingMb{slot, qbuf});
         qbuf = nullptr;                         // owned by the group now
+        note_held();
     } else {
         if ((rc = release_group(grp, ss))) return rc;
         if (two) {
@@ -899,6 +927,27 @@ size_t bp_stage_stash_bytes(const bp_stage_t* st) {
     if (!st) return 0;
     const Stage* s_ = (const Stage*)st;
     return (size_t)s_->L * s_->s_layer_bytes;
+}
+
+int bp_stage_held_bytes(const bp_stage_t* st, size_t* live_stash, size_t* group_stash, size_t* group_grads,
+                        size_t* peak_total) {
+    if (!st) return fail(BP_EINVAL, "stage handle is null");
+    const Stage* s_ = (const Stage*)st;
+    size_t h[3];
+    s_->held_bytes(h);
+    if (live_stash) *live_stash = h[0];
+    if (group_stash) *group_stash = h[1];
+    if (group_grads) *group_grads = h[2];
+    if (peak_total) *peak_total = s_->peak_held_bytes;
+    return BP_OK;
+}
+
+int bp_stage_reset_peak_bytes(bp_stage_t* st) {
+    if (!st) return fail(BP_EINVAL, "stage handle is null");
+    Stage* s_ = (Stage*)st;
+    s_->peak_held_bytes = 0;
+    s_->note_held();
+    return BP_OK;
 }
 
 int bp_stage_destroy(bp_stage_t* st) {
@@ -957,6 +1006,26 @@ int bp_prof_get(bp_stage_t* st, int kid, double* ms, long long* launches, double
     if (launches) *launches = s_->prof.launches[kid];
     if (flops) *flops = s_->prof.flops_total[kid];
     if (bytes) *bytes = s_->prof.bytes_total[kid];
+    return BP_OK;
+}
+
+int bp_prof_gemm_shapes(bp_stage_t* st) {
+    BP_ST(st);
+    if (s_->sync_all()) return BP_EHIP;
+    s_->prof.collect();
+    return (int)s_->prof.shapes.size();
+}
+
+int bp_prof_gemm_get(bp_stage_t* st, int index, int* dims, double* total_ms, long long* launches) {
+    BP_ST(st);
+    if (s_->sync_all()) return BP_EHIP;
+    s_->prof.collect();
+    if (index < 0 || index >= (int)s_->prof.shapes.size())
+        return fail(BP_EINVAL, "shape index %d out of range [0,%zu)", index, s_->prof.shapes.size());
+    const auto& sh = s_->prof.shapes[index];
+    if (dims) memcpy(dims, sh.dims, sizeof sh.dims);
+    if (total_ms) *total_ms = sh.ms;
+    if (launches) *launches = sh.launches;
     return BP_OK;
 }
 

@@ -820,11 +820,10 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     auto fill = [&](long t) { return t <= 0 ? 0.0 : (double)t / (double)(((t + ncu - 1) / ncu) * ncu); };
     const long t192 = (g.M % 256 == 0 && g.N % 192 == 0) ? (long)(g.M / 256) * (g.N / 192) : 0;
     // (the fused GELU-backward epilogue folds column sums over power-of-two lane groups: not 96 wide)
-    // With both operands read through the transpose path (weight gradients) and a long contraction
-    // the 192-wide tile runs its main loop at about two thirds of the 256-wide one's rate, so it
-    // has to fill the chip that much better to win (and a grid that leaves CUs free lets the other
-    // stream's kernels in); otherwise the two are within 5 %.
-    const double rate192 = (g.a_t && !g.b_t && (long)g.K * g.nseg >= 4096) ? 0.65 : 0.95;
+    // The 192-wide tile has fewer MFMAs per LDS read and per barrier: measured against the 256-wide
+    // one at equal fill it runs at about 0.85 of its rate with both operands read through the
+    // transpose path and a long contraction (weight gradients), else within 5 %.
+    const double rate192 = (g.a_t && !g.b_t && (long)g.K * g.nseg >= 4096) ? 0.85 : 0.95;
     if (g.epi == EPI_NONE && t192 >= most && rate192 * fill(t192) > fill(t256))
         return launch_dma<256, 192, 4, 2, 2>(g, s);
     // How many K slices the last, partly filled round of 256 x 256 tiles is cut into so that it fills
@@ -837,14 +836,9 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
         return splits;
     };
     if (t256 >= most) {
-        // tuning switch for A/B measurements: bit 3 of BITPIPE_DISABLE keeps the last round whole
-        static const bool split_tail = [] {
-            const char* dis = getenv("BITPIPE_DISABLE");
-            return !(dis && (strtol(dis, nullptr, 0) & 8));
-        }();
         const long full = (t256 / ncu) * ncu, tail = t256 - full;
         const int splits =
-            (split_tail && g.split_ws && g.epi == EPI_NONE && tail < most) ? tail_splits(tail) : 1;
+            (g.split_ws && g.epi == EPI_NONE && tail < most) ? tail_splits(tail) : 1;
         if (splits > 1) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, (int)full);
         return launch_dma<256, 256, 4, 2, 2>(g, s);
     }

@@ -31,7 +31,8 @@ def test_vmap_agrees_with_oracle(D):
     assert bp.bp_schedule_vmap(2, 0, D) == -1
 
 
-@pytest.mark.parametrize("D,N", [(2, 2), (2, 4), (4, 4), (4, 8), (4, 16), (6, 6), (6, 12), (8, 8)])
+@pytest.mark.parametrize("D,N", [(2, 2), (2, 4), (4, 4), (4, 8), (4, 16), (6, 6), (6, 12), (8, 8), (8, 16), (10, 10), (12, 12),
+                                 (16, 16)])
 def test_generated_order_is_the_oracles(D, N):
     order = bp.bp_schedule_generate(D, N)
     assert bp.ops_to_tuples(order) == [tuple(o) for o in so.generate(D, N)]
@@ -93,6 +94,16 @@ def test_simulate_reproduces_the_closed_forms_at_D4():
     order = bp.bp_schedule_generate(4, 4)
     ms, idle, peak = bp.bp_schedule_simulate(order, 4, 4)
     assert (ms, idle, peak) == (28, [4, 4, 4, 4], [7, 8, 8, 7])
+
+
+@pytest.mark.parametrize("D", [6, 8, 10, 12, 16])
+def test_simulate_reproduces_the_basic_unit_closed_forms_beyond_D4(D):
+    """Table 2 / Section 3.3 for N = D: makespan 2 (3N + D - 2) chunk slots, every device idle
+    2 (D - 2) of them (ratio (D-2)/(3N+D-2)), at most D M_a = 2D chunk stashes."""
+    order = bp.bp_schedule_generate(D, D)
+    ms, idle, peak = bp.bp_schedule_simulate(order, D, D)
+    assert ms == 8 * D - 4 and idle == [2 * (D - 2)] * D
+    assert max(peak) == 2 * D and min(peak) >= D + 3
 
 
 def test_generate_rejects_bad_arguments():

@@ -69,30 +69,57 @@ def test_generated_order_is_valid_and_conflict_free(D, N):
         assert sum(sl.end - sl.start for sl in lane) == 3 * 2 * N
 
 
-def test_basic_unit_closed_forms_D4():
-    """Section 3.3 / Table 2 at D = 4, N = 4, read from the golden fixture."""
-    (D, N, fb, bb, num, den, lo, hi), = _golden_rows()
+@pytest.mark.parametrize("row", _golden_rows())
+def test_basic_unit_closed_forms(row):
+    """Section 3.3 / Table 2 for the basic unit N = D at D = 4, 6, 8, 10, 12, 16, read from the golden
+    fixture (the paper's formulas evaluated at those D)."""
+    D, N, fb, bb, num, den, lo, hi = row
     D, N = int(D), int(N)
     lanes = so.generate_timeline(D, N)
+    assert so.conflicts(lanes) == 0 and so.validate(so.serialise(lanes), D, N) is None
     ms = so.makespan(lanes)
     # one device-forward = 2 chunk units; total time 3N + D - 2 device-forwards
-    assert ms == 2 * int(den) == 28
+    assert ms == 2 * int(den) == 8 * D - 4
     idle = so.idle_per_device(lanes)
     assert all(Fraction(i, ms) == Fraction(int(num), int(den)) for i in idle)
-    # idle = (D-2)/2 forward bubbles + (D-2)/4 backward bubbles = 1*2 + 0.5*4 chunk units
-    assert all(i == int(fb * 2 + bb * 4) for i in idle)
-    # activations between (D+3)/2 and D stage-activations = 7..8 chunk stashes
+    # idle = (D-2)/2 forward bubbles + (D-2)/4 backward bubbles, of 2 and 4 chunk units each
+    assert all(i == int(fb * 2 + bb * 4) == 2 * (D - 2) for i in idle)
+    # activations between (D+3)/2 and D stage-activations M_a (= 2 chunk stashes each): the busiest
+    # device holds exactly D M_a, none holds less than the lower end of the paper's range
     peaks = so.peak_stash(lanes)
-    assert min(peaks) == int(lo * 2) and max(peaks) == int(hi * 2)
-    assert peaks == [7, 8, 8, 7]
+    assert max(peaks) == int(hi * 2) == 2 * D
+    assert min(peaks) >= int(lo * 2) == D + 3
+    assert peaks == peaks[::-1]                       # the two pipelines mirror each other
+    if D == 4:
+        assert peaks == [7, 8, 8, 7]                  # here the lower end is reached too
+
+
+def test_rank_not_global_index_orders_the_backwards():
+    """Planted mistake: ranking backwards by the global micro-batch index (every down micro-batch
+    before every up one) instead of by the place in the own pipeline misses the closed form from
+    D = 6 on; the pins above would catch it."""
+    real = so.rank_in_pipeline
+    try:
+        so.rank_in_pipeline = lambda mb, D: mb
+        assert so.makespan(so.generate_timeline(6, 6)) > 8 * 6 - 4
+        assert so.makespan(so.generate_timeline(8, 8)) > 8 * 8 - 4
+    finally:
+        so.rank_in_pipeline = real
+    assert so.makespan(so.generate_timeline(6, 6)) == 44
 
 
 def test_concatenation_fills_tail_bubbles_D4():
     """Section 3.5: N = 2D must beat two basic units back to back (56) and cannot beat the
-    closed form 2*(3N + D - 2) = 52; the greedy order lands at 53."""
+    closed form 2*(3N + D - 2) = 52; the list-scheduled order lands at 53.  For N = K D the order
+    stays within 7 % of the closed form (D-2)/(3N+D-2) at the sizes below but does not reach it."""
     ms = so.makespan(so.generate_timeline(4, 8))
     assert 52 <= ms < 56
     assert ms == 53
+    for D, N in ((4, 12), (4, 16), (6, 12), (8, 16), (8, 24)):
+        closed = 6 * N + 2 * D - 4
+        got = so.makespan(so.generate_timeline(D, N))
+        assert closed <= got <= 1.07 * closed, (D, N, got, closed)
+        assert got < (N // D) * (8 * D - 4)            # better than units back to back
 
 
 def _golden_early_forward_rows():
