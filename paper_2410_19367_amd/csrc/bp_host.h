@@ -60,23 +60,49 @@ struct StashSlot {
 struct PendingMb { int slot; void* buf; };
 struct PendGroup { std::vector<PendingMb> items; };
 
-struct Stage {
+// Everything one stream pair needs to run forwards and backwards on its own: the streams, the
+// events that order the two, and the workspaces the kernels of a backward share.  A stage object has
+// one such lane for the calls of its C ABI; bp_run_schedule gives every virtual device (up to
+// kMaxLanes) a lane of its own, so that operations of different virtual devices, which are
+// independent within a time slot (Section 3.3: at most one operation per device and slot), run side
+// by side on the GPU.
+constexpr int kMaxLanes = 4;
+struct LaneState {
+    hipStream_t stream = nullptr;
+    // Weight-gradient GEMMs and the column reductions of the backward run on a second stream so
+    // that their memory-bound tails overlap the next data-gradient kernels; events order the two.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_ready[5] = {};         // main -> side: dz, du, dy, dqkv, da of the current layer
+    hipEvent_t ev_layer_done[2] = {};    // side -> main: workspaces of layer parity p are free again
+    bool layer_done_pending[2] = {false, false};
+    hipEvent_t ev_misc = nullptr;        // side -> main: end of the previous backward call
+    bool call_done_pending = false;
+    // lean mode: forward scratch for a, m, g; per contraction segment the recomputed a, m, g and
+    // throw-away LayerNorm statistics for the side stream's weight-gradient GEMMs
+    void *fw_a = nullptr, *fw_m = nullptr, *fw_g = nullptr;
+    void* re_x[3][kMaxGemmSegments] = {};    // [g | m | a][segment]
+    float* re_stats = nullptr;
+    std::vector<void*> pend_pool;                    // idle PendingMb buffers
+    // backward workspaces; those the side stream reads exist once per layer parity, dx rotates
+    // over three buffers (layer l writes l % 3, layer l-1 and its side work read it)
+    void *ws_big1[2] = {}, *ws_big2[2] = {}, *ws_h1[2] = {}, *ws_h2[2] = {}, *ws_h5[2] = {};
+    void *ws_h4 = nullptr, *ws_dx[3] = {};
+    void* ws_gout = nullptr;             // private copy of a backward's grad_out (lanes only)
+    float *ws_delta = nullptr, *ws_colsum[2] = {};
+    float* ws_splitk = nullptr;          // split-K partials of main-stream GEMMs: 4 * T * H floats
+    size_t ws_splitk_elems = 0;
+    float* ws_splitk_side = nullptr;     // the same for the weight-gradient GEMMs of the side stream
+    size_t ws_splitk_side_elems = 0;
+};
+
+struct Stage : LaneState {
     // shape
     int L = 0, H = 0, heads = 0, d = 0, S = 0, B = 0, T = 0, F = 0, n_chunks = 1;
     bool causal = true;
     int dtype = BP_BF16, max_inflight = 8;
     size_t esz = 2;
     float eps = 1e-5f;
-    hipStream_t stream = nullptr;
-    // Weight-gradient GEMMs and the column reductions of the backward run on a second stream so
-    // that their memory-bound tails overlap the next data-gradient kernels; events order the two.
-    hipStream_t side = nullptr;
     bool overlap = true;                 // false: everything on `stream` (also while timing kernels)
-    hipEvent_t ev_ready[5] = {};         // main -> side: dz, du, dy, dqkv, da of the current layer
-    hipEvent_t ev_layer_done[2] = {};    // side -> main: workspaces of layer parity p are free again
-    bool layer_done_pending[2] = {false, false};
-    hipEvent_t ev_misc = nullptr;        // side -> main: end of the previous backward call
-    bool call_done_pending = false;
 
     // parameters (matrices in the storage dtype, vectors fp32) and fp32 gradients per direction
     void* params = nullptr;
@@ -89,14 +115,8 @@ struct Stage {
     // Grouped weight gradients: per (direction, chunk) the micro-batches waiting for their group.
     int wgrad_group = 1;
     bool lean = false;                   // stash without LN outputs and GELU output: recomputed for the weight gradients
-    // lean mode: forward scratch for a, m, g; per contraction segment the recomputed a, m, g and
-    // throw-away LayerNorm statistics for the side stream's weight-gradient GEMMs
-    void *fw_a = nullptr, *fw_m = nullptr, *fw_g = nullptr;
-    void* re_x[3][kMaxGemmSegments] = {};    // [g | m | a][segment]
-    float* re_stats = nullptr;
     bool fuse_gelu = true;               // GELU forward/backward inside the GEMM epilogues when possible
     std::vector<PendGroup> pend[2];
-    std::vector<void*> pend_pool;                    // idle PendingMb buffers
     size_t q_dz = 0, q_du = 0, q_dy = 0, q_dqkv = 0, q_layer_bytes = 0;
     int slot_capacity = 8;                           // most live stashes (held ones come on top)
     // Each weight matrix is also kept transposed ([out,in]) so that the forward GEMMs read both
@@ -108,19 +128,25 @@ struct Stage {
     size_t s_layer_bytes = 0;
     std::vector<StashSlot> slots;
 
-    // backward workspaces
-    // backward workspaces; those the side stream reads exist once per layer parity, dx rotates
-    // over three buffers (layer l writes l % 3, layer l-1 and its side work read it)
-    void *ws_big1[2] = {}, *ws_big2[2] = {}, *ws_h1[2] = {}, *ws_h2[2] = {}, *ws_h5[2] = {};
-    void *ws_h4 = nullptr, *ws_dx[3] = {};
-    float *ws_delta = nullptr, *ws_colsum[2] = {};
-    float* ws_splitk = nullptr;          // split-K partials of main-stream GEMMs: 4 * T * H floats
-    size_t ws_splitk_elems = 0;
-    float* ws_splitk_side = nullptr;     // the same for the weight-gradient GEMMs of the side stream
-    size_t ws_splitk_side_elems = 0;
 
     // key-padding lengths per micro-batch (device int32 [B])
     std::map<int, int32_t*> lens;
+
+    // bp_run_schedule: one view of this object per lane.  A view shares the parameters and the
+    // gradient buffers (it does not own them) and has its own lane, stash slots, weight-gradient
+    // groups and clear flags: everything a (direction, stage) touches belongs to one virtual device,
+    // hence to one lane, so the views never write the same memory or the same host state.
+    bool is_view = false;
+    int device = 0;                      // HIP device the object lives on
+    std::vector<Stage*> views;
+    bool copy_grad_out = false;          // backward copies grad_out first (its side stream must not read caller memory)
+    int lane_alloc(LaneState& ln, bool with_stream);
+    void lane_free(LaneState& ln, bool with_stream);
+    int make_view(Stage** out);
+    int run_lanes(const Layout& L, const bp_op* order, int n_ops, int D, int N, int lanes, const void* inputs,
+                  const void* targets);
+    std::vector<hipEvent_t> sched_ev;    // bp_run_schedule: completion event of every op of the order
+    hipEvent_t ev_fork = nullptr;
 
     // buffers of bp_run_schedule, sized for sched_n micro-batches
     void *sched_act = nullptr, *sched_grad = nullptr;

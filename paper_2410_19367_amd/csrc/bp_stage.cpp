@@ -159,6 +159,7 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     st->max_inflight = opt.max_inflight ? opt.max_inflight : 8;
     st->eps = opt.ln_eps > 0 ? opt.ln_eps : 1e-5f;
     st->stream = (hipStream_t)opt.hip_stream;
+    if (hipGetDevice(&st->device) != hipSuccess) { delete st; return fail(BP_EHIP, "hipGetDevice failed"); }
     st->esz = dtype_size(st->dtype);
     st->lean = opt.stash_recompute == 1;
     st->wgrad_group = opt.wgrad_group ? opt.wgrad_group : std::min(kMaxGemmSegments, std::max(1, 16384 / st->T));
@@ -204,48 +205,9 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     st->q_dz = take(TH); st->q_du = take(TF); st->q_dy = take(TH); st->q_dqkv = take(3 * TH);
     st->q_layer_bytes = so;
 
-    // backward workspaces
-    const size_t big = std::max((size_t)st->F, (size_t)3 * st->H);
-    rc = BP_OK;
-    for (int p = 0; p < 2 && !rc; ++p) {
-        (rc = dev_alloc(&st->ws_big1[p], (size_t)st->T * big * st->esz)) ||
-            (rc = dev_alloc(&st->ws_big2[p], (size_t)st->T * 3 * st->H * st->esz)) ||
-            (rc = dev_alloc(&st->ws_h1[p], TH)) || (rc = dev_alloc(&st->ws_h2[p], TH)) ||
-            (rc = dev_alloc(&st->ws_h5[p], TH)) ||
-            (rc = dev_alloc((void**)&st->ws_colsum[p],
-                            std::max<size_t>(colsum_chunks(st->T) * ((size_t)9 * st->H + st->F), 1024) *
-                                sizeof(float)));
-    }
-    for (int i = 0; i < 3 && !rc; ++i) rc = dev_alloc(&st->ws_dx[i], TH);
-    if (!rc) rc = dev_alloc(&st->ws_h4, TH);
-    if (!rc && st->dtype == BP_BF16) {
-        st->ws_splitk_elems = (size_t)4 * st->T * st->H;
-        rc = dev_alloc((void**)&st->ws_splitk, st->ws_splitk_elems * sizeof(float));
-        // weight gradients with few output tiles (H x H, or a narrow MLP) and a long token axis
-        st->ws_splitk_side_elems = std::min((size_t)4 * st->H * std::max(st->H, st->F), (size_t)64 << 20);
-        if (!rc) rc = dev_alloc((void**)&st->ws_splitk_side, st->ws_splitk_side_elems * sizeof(float));
-    }
-    if (!rc && st->lean) {
-        (rc = dev_alloc(&st->fw_a, TH)) || (rc = dev_alloc(&st->fw_m, TH)) || (rc = dev_alloc(&st->fw_g, TF)) ||
-            (rc = dev_alloc((void**)&st->re_stats, (size_t)2 * st->T * sizeof(float)));
-        for (int i = 0; i < st->wgrad_group && !rc; ++i)
-            (rc = dev_alloc(&st->re_x[0][i], TF)) || (rc = dev_alloc(&st->re_x[1][i], TH)) ||
-                (rc = dev_alloc(&st->re_x[2][i], TH));
-    }
-    if (!rc) rc = dev_alloc((void**)&st->ws_delta, (size_t)st->B * st->heads * st->S * sizeof(float));
-    if (rc) { delete st; return rc; }
-
-    // second stream (default priority, not synchronising with the null stream) and its events
-    {
-        hipError_t e = hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking);
-        for (int i = 0; i < 5 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&st->ev_ready[i], hipEventDisableTiming);
-        for (int i = 0; i < 2 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&st->ev_layer_done[i], hipEventDisableTiming);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&st->ev_misc, hipEventDisableTiming);
-        if (e != hipSuccess) {
-            delete st;
-            return fail(BP_EHIP, "creating the side stream failed: %s", hipGetErrorString(e));
-        }
-    }
+    // lane 0: workspaces, the second stream (default priority, not synchronising with the null
+    // stream) and the events that order the two
+    if ((rc = st->lane_alloc(*st, false))) { delete st; return rc; }
 
     // initial values: zeros, LN gamma = 1
     hipError_t e = hipMemsetAsync(st->params, 0, n_layers * poff, st->stream);
@@ -267,39 +229,125 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     return BP_OK;
 }
 
+int Stage::lane_alloc(LaneState& ln, bool with_stream) {
+    const size_t TH = (size_t)T * H * esz, TF = (size_t)T * F * esz;
+    const size_t big = std::max((size_t)F, (size_t)3 * H);
+    int rc = BP_OK;
+    for (int p = 0; p < 2 && !rc; ++p) {
+        (rc = dev_alloc(&ln.ws_big1[p], (size_t)T * big * esz)) ||
+            (rc = dev_alloc(&ln.ws_big2[p], (size_t)T * 3 * H * esz)) ||
+            (rc = dev_alloc(&ln.ws_h1[p], TH)) || (rc = dev_alloc(&ln.ws_h2[p], TH)) ||
+            (rc = dev_alloc(&ln.ws_h5[p], TH)) ||
+            (rc = dev_alloc((void**)&ln.ws_colsum[p],
+                            std::max<size_t>(colsum_chunks(T) * ((size_t)9 * H + F), 1024) * sizeof(float)));
+    }
+    for (int i = 0; i < 3 && !rc; ++i) rc = dev_alloc(&ln.ws_dx[i], TH);
+    if (!rc) rc = dev_alloc(&ln.ws_h4, TH);
+    if (!rc) rc = dev_alloc(&ln.ws_gout, TH);
+    if (!rc && dtype == BP_BF16) {
+        ln.ws_splitk_elems = (size_t)4 * T * H;
+        rc = dev_alloc((void**)&ln.ws_splitk, ln.ws_splitk_elems * sizeof(float));
+        // weight gradients with few output tiles (H x H, or a narrow MLP) and a long token axis
+        ln.ws_splitk_side_elems = std::min((size_t)4 * H * std::max(H, F), (size_t)64 << 20);
+        if (!rc) rc = dev_alloc((void**)&ln.ws_splitk_side, ln.ws_splitk_side_elems * sizeof(float));
+    }
+    if (!rc && lean) {
+        (rc = dev_alloc(&ln.fw_a, TH)) || (rc = dev_alloc(&ln.fw_m, TH)) || (rc = dev_alloc(&ln.fw_g, TF)) ||
+            (rc = dev_alloc((void**)&ln.re_stats, (size_t)2 * T * sizeof(float)));
+        for (int i = 0; i < kMaxGemmSegments && !rc; ++i)
+            (rc = dev_alloc(&ln.re_x[0][i], TF)) || (rc = dev_alloc(&ln.re_x[1][i], TH)) ||
+                (rc = dev_alloc(&ln.re_x[2][i], TH));
+    }
+    if (!rc) rc = dev_alloc((void**)&ln.ws_delta, (size_t)B * heads * S * sizeof(float));
+    if (rc) return rc;
+    hipError_t e = hipSuccess;
+    if (with_stream) e = hipStreamCreateWithFlags(&ln.stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&ln.side, hipStreamNonBlocking);
+    for (int i = 0; i < 5 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ln.ev_ready[i], hipEventDisableTiming);
+    for (int i = 0; i < 2 && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ln.ev_layer_done[i], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ln.ev_misc, hipEventDisableTiming);
+    if (e != hipSuccess) return fail(BP_EHIP, "creating a lane's streams and events failed: %s", hipGetErrorString(e));
+    return BP_OK;
+}
+
+void Stage::lane_free(LaneState& ln, bool with_stream) {
+    if (ln.side) { hipStreamSynchronize(ln.side); hipStreamDestroy(ln.side); }
+    if (with_stream && ln.stream) { hipStreamSynchronize(ln.stream); hipStreamDestroy(ln.stream); }
+    for (auto e : ln.ev_ready) if (e) hipEventDestroy(e);
+    for (auto e : ln.ev_layer_done) if (e) hipEventDestroy(e);
+    if (ln.ev_misc) hipEventDestroy(ln.ev_misc);
+    for (auto b : ln.pend_pool) hipFree(b);
+    for (int p = 0; p < 2; ++p) {
+        hipFree(ln.ws_big1[p]); hipFree(ln.ws_big2[p]); hipFree(ln.ws_h1[p]); hipFree(ln.ws_h2[p]); hipFree(ln.ws_h5[p]);
+        hipFree(ln.ws_colsum[p]);
+    }
+    for (auto b : ln.ws_dx) hipFree(b);
+    hipFree(ln.ws_h4); hipFree(ln.ws_gout);
+    hipFree(ln.ws_splitk); hipFree(ln.ws_splitk_side);
+    hipFree(ln.fw_a); hipFree(ln.fw_m); hipFree(ln.fw_g); hipFree(ln.re_stats);
+    for (auto& row : ln.re_x) for (auto b : row) hipFree(b);
+    hipFree(ln.ws_delta);
+}
+
+// A view for one lane of bp_run_schedule: same shape, shared parameters and gradient buffers, own
+// lane (with a stream of its own), stash slots, groups and clear flags.
+int Stage::make_view(Stage** out) {
+    Stage* v = new (std::nothrow) Stage();
+    if (!v) return fail(BP_ENOMEM, "host allocation failed");
+    v->is_view = true;
+    v->device = device;
+    v->L = L; v->H = H; v->heads = heads; v->d = d; v->S = S; v->B = B; v->T = T; v->F = F; v->n_chunks = n_chunks;
+    v->causal = causal; v->dtype = dtype; v->max_inflight = max_inflight; v->esz = esz; v->eps = eps;
+    v->overlap = overlap; v->params = params; v->grads[0] = grads[0]; v->grads[1] = grads[1];
+    v->wgrad_group = wgrad_group; v->lean = lean; v->fuse_gelu = fuse_gelu;
+    v->q_dz = q_dz; v->q_du = q_du; v->q_dy = q_dy; v->q_dqkv = q_dqkv; v->q_layer_bytes = q_layer_bytes;
+    memcpy(v->p_off, p_off, sizeof p_off); memcpy(v->g_off, g_off, sizeof g_off);
+    v->p_layer_bytes = p_layer_bytes; v->g_layer_bytes = g_layer_bytes;
+    v->s_x = s_x; v->s_a = s_a; v->s_qkv = s_qkv; v->s_ctx = s_ctx; v->s_y = s_y; v->s_m = s_m; v->s_u = s_u; v->s_g = s_g;
+    v->s_mean1 = s_mean1; v->s_rstd1 = s_rstd1; v->s_mean2 = s_mean2; v->s_rstd2 = s_rstd2; v->s_lse = s_lse;
+    v->s_layer_bytes = s_layer_bytes;
+    v->slots.resize(max_inflight);
+    v->slot_capacity = slot_capacity;
+    v->pend[0].resize(n_chunks);
+    v->pend[1].resize(n_chunks);
+    v->grad_clean[0].assign(grad_clean[0].size(), 3);
+    v->grad_clean[1].assign(grad_clean[1].size(), 3);
+    int rc = v->lane_alloc(*v, true);
+    if (rc) { delete v; return rc; }
+    *out = v;
+    return BP_OK;
+}
+
 int Stage::sync_all() {
     hipError_t e = hipStreamSynchronize(stream);
     if (e == hipSuccess && side) e = hipStreamSynchronize(side);
     if (e != hipSuccess) return fail(BP_EHIP, "synchronise: %s", hipGetErrorString(e));
+    for (Stage* v : views) {
+        int rc = v->sync_all();
+        if (rc) return rc;
+    }
     return BP_OK;
 }
 
 Stage::~Stage() {
-    hipStreamSynchronize(stream);
-    if (side) { hipStreamSynchronize(side); hipStreamDestroy(side); }
-    for (auto e : ev_ready) if (e) hipEventDestroy(e);
-    for (auto e : ev_layer_done) if (e) hipEventDestroy(e);
-    if (ev_misc) hipEventDestroy(ev_misc);
-    hipFree(params);
-    hipFree(grads[0]);
-    hipFree(grads[1]);
-    for (auto& s : slots) { hipFree(s.buf); if (s.side_done) hipEventDestroy(s.side_done); }
+    sync_all();
+    for (Stage* v : views) delete v;
+    lane_free(*this, is_view);
+    if (!is_view) {
+        hipFree(params);
+        hipFree(grads[0]);
+        hipFree(grads[1]);
+        for (auto& kv : lens) hipFree(kv.second);
+    }
+    for (auto& s : slots) {
+        hipFree(s.buf);
+        if (s.side_done) hipEventDestroy(s.side_done);
+    }
     for (int dir = 0; dir < 2; ++dir)
         for (auto& grp : pend[dir])
             for (auto& it : grp.items) hipFree(it.buf);
-    for (auto b : pend_pool) hipFree(b);
-    for (int p = 0; p < 2; ++p) {
-        hipFree(ws_big1[p]); hipFree(ws_big2[p]); hipFree(ws_h1[p]); hipFree(ws_h2[p]); hipFree(ws_h5[p]);
-        hipFree(ws_colsum[p]);
-    }
-    for (auto b : ws_dx) hipFree(b);
-    hipFree(ws_h4);
-    hipFree(ws_splitk);
-    hipFree(fw_a); hipFree(fw_m); hipFree(fw_g); hipFree(re_stats);
-    for (auto& row : re_x) for (auto b : row) hipFree(b);
-    hipFree(ws_splitk_side);
-    hipFree(ws_delta);
-    for (auto& kv : lens) hipFree(kv.second);
+    for (auto e : sched_ev) if (e) hipEventDestroy(e);
+    if (ev_fork) hipEventDestroy(ev_fork);
     hipFree(sched_act); hipFree(sched_grad); hipFree(sched_loss);
 }
 
@@ -611,6 +659,7 @@ int Stage::acquire_slot(int chunk, int mb, int* out) {
         if (e != hipSuccess) return fail(BP_EHIP, "stash reuse wait: %s", hipGetErrorString(e));
         sl.side_pending = false;
     }
+
     sl.live = true; sl.chunk = chunk; sl.mb = mb;
     *out = pick;
     return BP_OK;
@@ -771,6 +820,11 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         void* keep = qbuf + (size_t)(L - 1) * q_layer_bytes + q_dz;
         BP_HIP(hipMemcpyAsync(keep, grad_out, (size_t)T * H * esz, hipMemcpyDeviceToDevice, stream));
         dz = keep;
+    } else if (copy_grad_out) {
+        // lanes of bp_run_schedule: the next stage's backward (another lane) rewrites grad_out as soon
+        // as this call's main stream is through, so the side stream reads a private copy
+        BP_HIP(hipMemcpyAsync(ws_gout, grad_out, (size_t)T * H * esz, hipMemcpyDeviceToDevice, stream));
+        dz = ws_gout;
     }
     for (int l = L - 1; l >= 0; --l) {
         const int p = l & 1;

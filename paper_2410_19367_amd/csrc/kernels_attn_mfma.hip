@@ -15,6 +15,8 @@
 // One swizzle serves plain 16-byte fragment reads and transpose reads of the same tile:
 // chunk c of row r is stored at c ^ f(r), f chosen so that 16 consecutive rows (plain reads) and
 // 4 consecutive rows x 64 bytes (transpose reads) both cover all banks.
+#include <atomic>
+
 #include "bp_kernels.h"
 #include "bp_device.h"
 
@@ -646,12 +648,14 @@ static hipError_t set_smem(K kern, size_t smem) {
 // heaviest causal block, which is what bounds a launch with only a couple of blocks per CU; with
 // many blocks per CU the 4-wave form with two co-resident blocks is faster.
 static int tiles_per_step(const AttnArgs& a) {
-    static int n_cu = 0;
+    static std::atomic<int> n_cu_cached{0};
+    int n_cu = n_cu_cached.load(std::memory_order_relaxed);
     if (!n_cu) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
             n_cu = 256;
+        n_cu_cached.store(n_cu, std::memory_order_relaxed);
     }
     const long blocks = (long)(a.S / 64) * a.heads * a.B;
     return (a.S >= 512 && blocks <= 2L * n_cu) ? 2 : 1;
@@ -664,11 +668,11 @@ static hipError_t launch_fwd_nt(const AttnArgs& a, hipStream_t s) {
     const size_t stages = (size_t)2 * NT * 2 * 64 * D * 2;
     const size_t merge = (size_t)2 * (2 * NT - 1) * ((D / 32) * 16 * 64 + 128) * sizeof(float);
     const size_t smem = stages > merge ? stages : merge;
-    static bool set = false;
-    if (!set) {
+    static std::atomic<bool> set{false};   // several host threads may launch at once
+    if (!set.load(std::memory_order_acquire)) {
         hipError_t e = set_smem(attn_fwd_mfma_kernel<D, DR, NT>, smem);
         if (e != hipSuccess) return e;
-        set = true;
+        set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, DR, NT>), grid, block, smem, s, a, scale);
     return hipGetLastError();
@@ -692,12 +696,12 @@ static hipError_t launch_bwd_t(const AttnArgs& a, hipStream_t s) {
     const float scale = 1.f / sqrtf((float)a.d);
     const dim3 grid((a.S / 64) * a.heads * a.B), block(256);
     const size_t smem = 2 * 2 * 64 * D * 2, smem2 = 2 * (2 * 64 * D * 2 + 512);
-    static bool set = false;
-    if (!set) {
+    static std::atomic<bool> set{false};   // several host threads may launch at once
+    if (!set.load(std::memory_order_acquire)) {
         hipError_t e = set_smem(attn_bwd_dq_mfma_kernel<D, DR>, smem);
         if (e == hipSuccess) e = set_smem(attn_bwd_dkv_mfma_kernel<D, DR>, smem2);
         if (e != hipSuccess) return e;
-        set = true;
+        set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, DR>), grid, block, smem, s, a, scale);
     hipLaunchKernelGGL((attn_bwd_dkv_mfma_kernel<D, DR>), grid, block, smem2, s, a, scale);

@@ -17,6 +17,8 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include <atomic>
+
 #include "bp_kernels.h"
 #include "bp_device.h"
 
@@ -661,12 +663,12 @@ static hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
 #define BP_GEMM_LAUNCH(AR, BR)                                                                   \
     do {                                                                                         \
         auto kern = gemm_mfma_kernel<BM, BN, WM, WN, AR, BR, RAGGED>;                            \
-        static bool attr_set = false;   /* once per instantiation */                             \
-        if (smem > 64 * 1024 && !attr_set) {                                                     \
+        static std::atomic<bool> attr_set{false};   /* once per instantiation; host threads may race */ \
+        if (smem > 64 * 1024 && !attr_set.load(std::memory_order_acquire)) {                                                     \
             hipError_t e = hipFuncSetAttribute((const void*)kern,                                \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
             if (e != hipSuccess) return e;                                                       \
-            attr_set = true;                                                                     \
+            attr_set.store(true, std::memory_order_release);                                     \
         }                                                                                        \
         hipLaunchKernelGGL(kern, grid, block, smem, s, g, tiles_m, tiles_n);                     \
     } while (0)
@@ -738,12 +740,12 @@ static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1, i
 #define BP_GEMM_LAUNCH(AR, BR)                                                                   \
     do {                                                                                         \
         auto kern = gemm_dma_kernel<BM, BN, WM, WN, BKT, NS, AR, BR>;                            \
-        static bool attr_set = false;   /* once per instantiation */                             \
-        if (smem > 64 * 1024 && !attr_set) {                                                     \
+        static std::atomic<bool> attr_set{false};   /* once per instantiation; host threads may race */ \
+        if (smem > 64 * 1024 && !attr_set.load(std::memory_order_acquire)) {                                                     \
             hipError_t e = hipFuncSetAttribute((const void*)kern,                                \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
             if (e != hipSuccess) return e;                                                       \
-            attr_set = true;                                                                     \
+            attr_set.store(true, std::memory_order_release);                                     \
         }                                                                                        \
         hipLaunchKernelGGL(kern, grid, block, smem, s, g, tiles_m, tiles_n, splits, n_full);     \
     } while (0)
@@ -789,12 +791,14 @@ bool gemm_can_fuse_epilogue(int dtype, const GemmArgs& g) {
 }
 
 static int cu_count() {
-    static int n = 0;
+    static std::atomic<int> cached{0};
+    int n = cached.load(std::memory_order_relaxed);
     if (!n) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
             n = 256;
+        cached.store(n, std::memory_order_relaxed);
     }
     return n;
 }
