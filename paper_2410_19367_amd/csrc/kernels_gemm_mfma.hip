@@ -846,17 +846,27 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
         if (splits > 1) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, (int)full);
         return launch_dma<256, 256, 4, 2, 2>(g, s);
     }
-    // Few output tiles but a long K: 256x256 tiles on K slices keep the operand traffic per flop
-    // at the large-tile level (128x128 tiles are bound by the per-CU load path); measured to win
-    // from five eighths of the CUs on.
+    // Too few 256 x 256 tiles to fill the chip.  Up to a contraction depth of 4096, 128 x 128 tiles
+    // that do fill it win over large tiles cut along K: one launch, no fp32 partials (inside the
+    // BERT-style stage, 4096 x 1024 x 3072: 41.7 us against 48.6 us).  Deeper than that the small tiles
+    // lose: they move twice the operand bytes per flop, and inside a layer those come from HBM,
+    // not from a warm cache (2048 x 2048 x 8192: 96 us against 84 us; 2048 x 2560 x 10240: 229 against 115).
+    // Not for weight gradients either: with both operands read through the transpose path the small
+    // tiles lose more than the partials cost (2560 x 2560 x 16384: 334 us against 272 us).
+    const long t128 = (long)(g.M / 128) * (g.N / 128);
+    if (t128 >= most && k_total <= 4096 && !(g.a_t && !g.b_t)) {
+        if (g.K % 128 == 0) return launch_dma<128, 128, 2, 4, 2, 128>(g, s);
+        return launch_dma<128, 128, 2, 4, 2>(g, s);
+    }
+    // Fewer tiles than that but a long K: 256 x 256 tiles on K slices keep the operand traffic per
+    // flop at the large-tile level (128 x 128 tiles are bound by the per-CU load path).
     if (t256 > 0 && g.split_ws && g.epi == EPI_NONE) {
         const int splits = tail_splits(t256);
         if (splits > 1 && t256 * splits * 8 >= 5L * ncu) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, 0);
     }
     // Small outputs (128 x 128 tiles on fewer than three quarters of the CUs) with a long K: the same split, on the small
     // tiles (slices at least 1024 deep: below that the second kernel costs what the split gains)
-    const long t128 = (long)(g.M / 128) * (g.N / 128);
-    if (t128 < most && g.split_ws && g.epi == EPI_NONE) {
+    if (g.split_ws && g.epi == EPI_NONE) {
         const int bk = g.K % 128 == 0 ? 128 : BK;
         int splits = (int)(ncu / t128);
         if (splits > 4) splits = 4;
