@@ -509,10 +509,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
             // every LDS read of slice kt has returned (the last ones feed the MFMAs below) and this
             // wave's part of slice kt+1 has landed: the barrier publishes that slice and frees the
             // stage of slice kt
+            // (a bare s_barrier: __syncthreads() carries a release fence, for which the compiler waits
+            // for every outstanding load, those of the slices further ahead included)
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0)
             BP_WAIT_VMCNT((NS - 2) * LPT);
-            __syncthreads();
+            __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             const int nxt = cur + 1 == NS ? 0 : cur + 1;
             read_step(smem + nxt * STAGE, 0, 0);
