@@ -1,4 +1,5 @@
-// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation) for the
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_16x16x32_bf16 in the 256 x 256 tiles,
+// v_mfma_f32_32x32x16_bf16 in the others; fp32 accumulation) for the
 // three shapes of a linear layer: forward Y = X W (+b)(+res), dgrad dX = dY W^T, wgrad dW += X^T dY.
 //
 // A block computes a BM x BN tile of C, stepping over K in slices of BK = 64.  Each slice of
@@ -311,6 +312,29 @@ __device__ __forceinline__ bf16x8 read_frag2(const char* lds, int row0, int kk, 
     }
 }
 
+// The same for the 16x16x32 MFMA shape: 8 consecutive k (k32 step kk, quarter lane/16) of row
+// (row0 + lane%16).
+template <int R, int BKT, bool RMAJOR>
+__device__ __forceinline__ bf16x8 read_frag16(const char* lds, int row0, int kk, int lane) {
+    const int g4 = lane >> 4;
+    if (!RMAJOR) {
+        return *reinterpret_cast<const bf16x8*>(lds + kmaj_off<BKT>(row0 + (lane & 15), kk * 4 + g4));
+    } else {
+        const int i = lane & 15;
+        const int r = i >> 2, q = i & 3;
+        const int col = row0 + 4 * q;
+        const int chunk = col >> 3, byte = (col & 7) * 2;
+        const int k0 = kk * 32 + 8 * g4;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(lds + rmajor_off<R>(k0 + r, chunk) + byte));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(lds + rmajor_off<R>(k0 + 4 + r, chunk) + byte));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, v);
+    }
+}
+
 constexpr int rows_per_instr(int lanes_per_row) {
     int r = 1;
     while (2 * r * lanes_per_row <= 64 && 2 * r <= 32) r *= 2;
@@ -351,7 +375,7 @@ struct SchedRounds {
     }
 };
 
-template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR>
+template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR, bool MI16 = false>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n, int splits,
                                                                int n_full) {
     constexpr int NW = WM * WN;
@@ -421,42 +445,77 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     pb.init(wave, lane, g.ldb);
     constexpr int LPT = decltype(pa)::NI + decltype(pb)::NI;   // loads per slice per wave
 
-    f32x16 acc[TM][TN];
+    // MI16: the tile is made of 16x16x32 MFMAs instead of 32x32x16 ones, and a "k step" below is 32
+    // deep instead of 16.  Per flop that shape reads and writes half as many accumulator registers;
+    // under sustained load, where the chip runs against its power limit, a loop of nothing but MFMAs
+    // on random operands reaches 1.9 PFLOP/s with it against 1.35 - 1.65 with the 32x32x16 shape
+    // (two waves per SIMD; one wave alone cannot issue the 16-cycle instructions back to back).  Inside
+    // the stages the 256 x 256 tiles gain 2 % (step time), the weight-gradient form 4 - 6 %; on the
+    // 192-wide and the 128 x 128 tiles it made no difference, so those keep the 32x32x16 shape.
+    typedef float f32x4acc __attribute__((ext_vector_type(4)));
+    constexpr int FM = MI16 ? BM / WM / 16 : TM, FN = MI16 ? BN / WN / 16 : TN;   // fragments per k step
+    f32x16 acc[MI16 ? 1 : TM][MI16 ? 1 : TN];
+    f32x4acc acc16[MI16 ? FM : 1][MI16 ? FN : 1];
+    if constexpr (MI16) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc16[i][j][v] = 0.f;
+    } else {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    }
 
-    constexpr int KK = BKT / 16;
-    static_assert(KK >= 2 && KK % 2 == 0, "a K slice is an even number of k16 steps");
+    constexpr int KK = MI16 ? BKT / 32 : BKT / 16;
+    static_assert(KK >= 2 && KK % 2 == 0, "a K slice is an even number of k steps");
     static_assert(NS >= 2 && NS <= 5, "2 to 5 LDS stages");
     static_assert((NS - 2) * LPT < 64, "outstanding loads must fit the vmcnt field");
-    constexpr int NREAD = (TM * (A_RMAJOR ? 2 : 1) + TN * (B_RMAJOR ? 2 : 1));   // LDS reads per k16 step
-    bf16x8 fa[2][TM], fb[2][TN];
+    constexpr int NREAD = (FM * (A_RMAJOR ? 2 : 1) + FN * (B_RMAJOR ? 2 : 1));   // LDS reads per k step
+    bf16x8 fa[2][FM], fb[2][FN];
     // program order = issue order of the reads: the fragments the step's first MFMAs need (A row
     // block 0 and every B column block) before the other A row blocks
     auto read_step = [&](const char* sa, int kk, int buf) {
         const char* sb = sa + A_BYTES;
+        if constexpr (MI16) {
+            fa[buf][0] = read_frag16<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM), kk, lane);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) fb[buf][j] = read_frag16<BN, BKT, B_RMAJOR>(sb, wn * (BN / WN) + j * 16, kk, lane);
+#pragma unroll
+            for (int i = 1; i < FM; ++i) fa[buf][i] = read_frag16<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 16, kk, lane);
+        } else {
         fa[buf][0] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM), kk, lane);
 #pragma unroll
         for (int j = 0; j < TN; ++j) fb[buf][j] = read_frag2<BN, BKT, B_RMAJOR>(sb, wn * (BN / WN) + j * 32, kk, lane);
 #pragma unroll
         for (int i = 1; i < TM; ++i) fa[buf][i] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 32, kk, lane);
+        }
     };
     auto mfma_step = [&](int buf) {
+        if constexpr (MI16) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[buf][i], fb[buf][j], acc16[i][j], 0, 0, 0);
+        } else {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+        }
     };
     // Issue order inside a k16 step, pinned completely (an MFMA left out of the groups could drift
     // across the slice boundary): the LDS reads of the next step spread over the first MFMAs.  At a
     // slice boundary the MFMAs of the slice's last k16 step also carry the direct-to-LDS loads of the
     // slice NS ahead.
-    constexpr int NMFMA = TM * TN;
+    constexpr int NMFMA = FM * FN;
     auto interleave = [&]() { SchedRounds<0, NMFMA, NREAD, 0>::apply(); };
     auto interleave_boundary = [&]() { SchedRounds<0, NMFMA, NREAD, LPT>::apply(); };
     // wait until at most `n` of the most recently requested slices are still on their way
@@ -568,11 +627,22 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
                                                           n_base + (lane % ELPR) * 8);
             }
         }
+        if constexpr (MI16) {
+            // lane l holds column l % 16 and rows 4 * (l / 16) .. + 3 of every 16 x 16 tile
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        ep[(16 * i2 + 4 * (lane >> 4) + v) * PITCH + j * 16 + (lane & 15)] = acc16[2 * i + i2][j][v];
+        } else {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 ep[(8 * (v >> 2) + 4 * h + (v & 3)) * PITCH + j * 32 + (lane & 31)] = acc[i][j][v];
+        }
         // rows per instruction: the largest power of two whose lanes fit in a wave (a 96-wide wave
         // tile leaves a quarter of the lanes idle here)
         if (is_split) {             // fp32 partial of this K slice: [tail tile][slice][BM][BN]
@@ -728,7 +798,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int spli
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NS, int BKT = 64>
+template <int BM, int BN, int WM, int WN, int NS, int BKT = 64, bool MI16 = false>
 static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1, int n_full = -1) {
     const int tiles_m = g.M / BM, tiles_n = g.N / BN;
     const int nblk = tiles_m * tiles_n;
@@ -741,7 +811,7 @@ static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1, i
     const size_t smem = stages > epilogue ? stages : epilogue;
 #define BP_GEMM_LAUNCH(AR, BR)                                                                   \
     do {                                                                                         \
-        auto kern = gemm_dma_kernel<BM, BN, WM, WN, BKT, NS, AR, BR>;                            \
+        auto kern = gemm_dma_kernel<BM, BN, WM, WN, BKT, NS, AR, BR, MI16>;                         \
         static std::atomic<bool> attr_set{false};   /* once per instantiation; host threads may race */ \
         if (smem > 64 * 1024 && !attr_set.load(std::memory_order_acquire)) {                                                     \
             hipError_t e = hipFuncSetAttribute((const void*)kern,                                \
@@ -845,8 +915,8 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
         const long full = (t256 / ncu) * ncu, tail = t256 - full;
         const int splits =
             (g.split_ws && g.epi == EPI_NONE && tail < most) ? tail_splits(tail) : 1;
-        if (splits > 1) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, (int)full);
-        return launch_dma<256, 256, 4, 2, 2>(g, s);
+        if (splits > 1) return launch_dma<256, 256, 2, 4, 2, 64, true>(g, s, splits, (int)full);
+        return launch_dma<256, 256, 2, 4, 2, 64, true>(g, s);
     }
     // Too few 256 x 256 tiles to fill the chip.  Up to a contraction depth of 4096, 128 x 128 tiles
     // that do fill it win over large tiles cut along K: one launch, no fp32 partials (inside the
@@ -864,7 +934,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     // flop at the large-tile level (128 x 128 tiles are bound by the per-CU load path).
     if (t256 > 0 && g.split_ws && g.epi == EPI_NONE) {
         const int splits = tail_splits(t256);
-        if (splits > 1 && t256 * splits * 8 >= 5L * ncu) return launch_dma<256, 256, 4, 2, 2>(g, s, splits, 0);
+        if (splits > 1 && t256 * splits * 8 >= 5L * ncu) return launch_dma<256, 256, 2, 4, 2, 64, true>(g, s, splits, 0);
     }
     // Small outputs (128 x 128 tiles on fewer than three quarters of the CUs) with a long K: the same split, on the small
     // tiles (slices at least 1024 deep: below that the second kernel costs what the split gains)
