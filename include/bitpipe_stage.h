@@ -153,6 +153,14 @@ int bp_stage_backward(bp_stage_t* st, int chunk, int mb, const void* grad_out, v
 int bp_stage_backward_dir(bp_stage_t* st, int chunk, int mb, const void* grad_out,
                           void* grad_in, int direction);
 
+/* Add the direction-1 accumulators into the direction-0 ones and clear direction 1: the sum that
+ * stands in, on one device, for the all-reduce between the two replicas of a stage (Section 3.4).
+ * bp_run_schedule does this at the end of an iteration; a caller that drives the two pipelines
+ * itself with bp_stage_backward_dir calls it before bp_stage_get_grad, which reads direction 0.
+ * Completes the weight-gradient groups still open first.  Asynchronous (enqueued on the object's
+ * streams; bp_stage_get_grad synchronises).  Calling it twice in a row adds nothing the second time. */
+int bp_stage_merge_directions(bp_stage_t* st);
+
 /* One operation of a schedule: forward or backward of global stage `stage` (= chunk index) on
  * micro-batch `mb`, in pipeline `dir`, placed on virtual device `vdev`. */
 typedef struct bp_op {

@@ -24,7 +24,7 @@ KERNEL_IDS = {n: i for i, n in enumerate(
 # every symbol include/bitpipe_stage.h declares
 EXPORTS = (
     "bp_stage_init", "bp_stage_init_ex", "bp_stage_stash_bytes", "bp_stage_held_bytes", "bp_stage_reset_peak_bytes", "bp_stage_destroy", "bp_stage_set_param",
-    "bp_stage_get_grad", "bp_stage_zero_grad", "bp_stage_set_seqlens", "bp_stage_forward",
+    "bp_stage_get_grad", "bp_stage_zero_grad", "bp_stage_merge_directions", "bp_stage_set_seqlens", "bp_stage_forward",
     "bp_stage_backward", "bp_stage_backward_dir", "bp_schedule_vmap", "bp_schedule_generate",
     "bp_schedule_validate", "bp_schedule_simulate", "bp_run_schedule", "bp_schedule_vmap_ex",
     "bp_schedule_generate_ex", "bp_schedule_validate_ex", "bp_schedule_simulate_ex", "bp_run_schedule_ex",
@@ -80,6 +80,7 @@ def lib():
         l.bp_stage_set_param.argtypes = [vp, ci, ci, ci, vp, C.c_size_t]
         l.bp_stage_get_grad.argtypes = [vp, ci, ci, ci, vp, C.c_size_t]
         l.bp_stage_zero_grad.argtypes = [vp]
+        l.bp_stage_merge_directions.argtypes = [vp]
         l.bp_stage_set_seqlens.argtypes = [vp, ci, vp]
         l.bp_stage_forward.argtypes = [vp, ci, ci, vp, vp]
         l.bp_stage_backward.argtypes = [vp, ci, ci, vp, vp]
@@ -196,6 +197,10 @@ def bp_stage_get_grad(st, chunk, layer, tensor_id, shape) -> np.ndarray:
 
 def bp_stage_zero_grad(st):
     return _check(lib().bp_stage_zero_grad(st))
+
+
+def bp_stage_merge_directions(st):
+    return _check(lib().bp_stage_merge_directions(st))
 
 
 def bp_stage_set_seqlens(st, mb, lens):

@@ -1025,6 +1025,10 @@ int bp_stage_zero_grad(bp_stage_t* st) {
     BP_ST(st);
     return s_->zero_grad();
 }
+int bp_stage_merge_directions(bp_stage_t* st) {
+    BP_ST(st);
+    return s_->merge_directions();
+}
 int bp_stage_set_seqlens(bp_stage_t* st, int mb, const int32_t* lens) {
     BP_ST(st);
     return s_->set_seqlens(mb, lens);

@@ -147,6 +147,14 @@ def test_grouped_weight_gradients_interleaved_chunks_and_directions():
             for name in si.PARAM_NAMES:
                 err = hz.rel_err(g.grad(c, 0, name), orc.grads[0][c][0][name])
                 assert err <= hz.TOL[cfg.dtype], (c, name, err)
+        # the sum of the two replicas (Section 3.4): direction 1 is added into direction 0, once
+        for rep in range(2):
+            g.bp.bp_stage_merge_directions(g.h)
+            for c in range(2):
+                for name in si.PARAM_NAMES:
+                    want = orc.grads[0][c][0][name] + orc.grads[1][c][0][name]
+                    err = hz.rel_err(g.grad(c, 0, name), want)
+                    assert err <= hz.TOL[cfg.dtype], (rep, c, name, err)
 
 
 @pytest.mark.parametrize("group", [1, 3, 5])
