@@ -44,8 +44,10 @@ __device__ __forceinline__ int kmajor_off(int row, int chunk) {
 // pieces into different 64-byte bank groups.  With R a multiple of 128 the rows start 0 mod 256
 // bytes apart (shift by 0/64/128/192 bytes); with R = 192 they alternate 0/128, so rows 2 and 3
 // only need a 64-byte shift, which also keeps the XOR inside the row's 24 chunks.
+// (The 16x16x32 MFMA shape reads k-rows k .. k+3 and k+8 .. k+11 in one pass of 32 lanes: bit 3 of k
+// moves a piece by another 32 bytes.)
 template <int R> __device__ __forceinline__ int rmajor_swz(int k) {
-    return R % 128 == 0 ? ((k & 3) << 2) : (((k >> 1) & 1) << 2);
+    return R % 128 == 0 ? (((k & 3) << 2) | (((k >> 3) & 1) << 1)) : (((k >> 1) & 1) << 2);
 }
 template <int R>
 __device__ __forceinline__ int rmajor_off(int k, int chunk) {
