@@ -377,7 +377,7 @@ struct SchedRounds {
     }
 };
 
-template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR, bool MI16 = false>
+template <int BM, int BN, int WM, int WN, int BKT, int NS, bool A_RMAJOR, bool B_RMAJOR, bool MI16 = false, bool RING = false>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int tiles_m, int tiles_n, int splits,
                                                                int n_full) {
     constexpr int NW = WM * WN;
@@ -483,13 +483,14 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     // program order = issue order of the reads: the fragments the step's first MFMAs need (A row
     // block 0 and every B column block) before the other A row blocks
     auto read_step = [&](const char* sa, int kk, int buf) {
-        const char* sb = sa + A_BYTES;
+        constexpr int LBK = RING ? 32 : BKT;            // K depth of one LDS tile (ring: slots of 32)
+        const char* sb = sa + BM * LBK * 2;
         if constexpr (MI16) {
-            fa[buf][0] = read_frag16<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM), kk, lane);
+            fa[buf][0] = read_frag16<BM, LBK, A_RMAJOR>(sa, wm * (BM / WM), kk, lane);
 #pragma unroll
-            for (int j = 0; j < FN; ++j) fb[buf][j] = read_frag16<BN, BKT, B_RMAJOR>(sb, wn * (BN / WN) + j * 16, kk, lane);
+            for (int j = 0; j < FN; ++j) fb[buf][j] = read_frag16<BN, LBK, B_RMAJOR>(sb, wn * (BN / WN) + j * 16, kk, lane);
 #pragma unroll
-            for (int i = 1; i < FM; ++i) fa[buf][i] = read_frag16<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM) + i * 16, kk, lane);
+            for (int i = 1; i < FM; ++i) fa[buf][i] = read_frag16<BM, LBK, A_RMAJOR>(sa, wm * (BM / WM) + i * 16, kk, lane);
         } else {
         fa[buf][0] = read_frag2<BM, BKT, A_RMAJOR>(sa, wm * (BM / WM), kk, lane);
 #pragma unroll
@@ -538,6 +539,89 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
     // the last one again (into stages nobody reads any more) and past the last slice it reads
     // fragments nobody uses; the change from one contraction segment to the next happens between
     // runs of the loop.
+    if constexpr (RING) {
+        // Ring mode (the weight-gradient form): five LDS slots of 32 along K, one k step each (5 x 32 KB
+        // for a 256 x 256 tile: the whole LDS), instead of two stages of 64.  An iteration still covers
+        // 64 of K with one barrier between its two k steps.  Past the barrier it requests the slot that
+        // the iteration after next reads first, into the first slot it has just freed; the second freed
+        // slot is requested one k step later, in the next iteration's first step, and has a barrier
+        // more to land: the barrier only ever waits for the older of the two requests, and the loads
+        // reach the CU's load path in two bursts per iteration instead of one.  Measured on the
+        // weight-gradient shapes of the GPT-style stages: +13 % (2048 x 8192 x 16384: 1130 -> 1280
+        // TFLOP/s); with both operands contraction-major it is 2 % slower than two stages, so those
+        // keep them.
+        static_assert(!RING || (MI16 && BKT == 64 && NS == 5), "ring mode: 16x16x32 MFMAs, five slots of 32");
+        constexpr int SLOT = (BM + BN) * 32 * 2;
+        DmaPlan<BM, 32, NW, A_RMAJOR> ra;
+        DmaPlan<BN, 32, NW, B_RMAJOR> rb;
+        ra.init(wave, lane, g.lda);
+        rb.init(wave, lane, g.ldb);
+        constexpr int L32 = decltype(ra)::NI + decltype(rb)::NI;    // loads per slot per wave
+        const int nq = 2 * nk;                                      // slots this block walks through
+        const uint32_t a_step32 = a_step / 2, b_step32 = b_step / 2;
+        auto request = [&](int slot) {
+            ra.issue(a_tile, a_off, smem + slot * SLOT, wave);
+            rb.issue(b_tile, b_off, smem + slot * SLOT + BM * 64, wave);
+            // (no branch) past the end the last slot is requested again, into slots nobody reads any more
+            ++issued;
+            a_off += issued < nq ? a_step32 : 0u;
+            b_off += issued < nq ? b_step32 : 0u;
+        };
+        auto interleave_l = [&]() { SchedRounds<0, NMFMA, NREAD, L32>::apply(); };
+        // The requests walk through the contraction segments 32 deep at a time; a segment holds an even
+        // number of slots and the loop requests two per iteration, so the change from one segment to
+        // the next falls between two runs of the (branch-free) loop, as in the staged loop below.
+        const int nq_seg = 2 * nk_seg;
+        int kl32 = 2 * kl;                                          // slots requested so far in the current segment
+        auto next_segment = [&]() {
+            if (issued < nq && kl32 == nq_seg) {
+                kl32 = 0;
+                ++seg;
+                a_tile = a_origin(seg);
+                b_tile = b_origin(seg);
+                a_off = b_off = 0;
+            }
+        };
+        a_off = (uint32_t)kl32 * a_step32;
+        b_off = (uint32_t)kl32 * b_step32;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            request(q);
+            ++kl32;
+            next_segment();
+        }
+        BP_WAIT_VMCNT(2 * L32);                                     // slots 0 and 1 have landed
+        __builtin_amdgcn_s_barrier();
+        read_step(smem, 0, 0);
+        int s0 = 0;                                                 // slot of the first half of the current slice
+        int late = 4;                                               // slot of the request that has a barrier more to land
+        int it = 0;
+        while (it < nk) {
+            const int run = issued < nq ? min(nk - it, (nq_seg - kl32) / 2) : nk - it;
+            for (int r = 0; r < run; ++r) {
+                const int s1 = s0 + 1 >= 5 ? s0 - 4 : s0 + 1;
+                const int n0 = s0 + 2 >= 5 ? s0 - 3 : s0 + 2;
+                read_step(smem + s1 * SLOT, 0, 1);
+                request(late);
+                mfma_step(0);
+                interleave_l();
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0)
+                BP_WAIT_VMCNT(L32);                          // only the request just made may still be on its way
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                read_step(smem + n0 * SLOT, 0, 0);
+                request(s0);
+                late = s1;
+                mfma_step(1);
+                interleave_l();
+                s0 = n0;
+            }
+            it += run;
+            kl32 += 2 * run;
+            next_segment();
+        }
+    } else {
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) {
         if (s < nk) {
@@ -599,6 +683,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
             b_tile = b_origin(seg);
             a_off = b_off = 0;
         }
+    }
     }
     BP_WAIT_VMCNT(0);                                   // the repeated requests too have landed
 
@@ -800,7 +885,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g, int spli
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NS, int BKT = 64, bool MI16 = false>
+template <int BM, int BN, int WM, int WN, int NS, int BKT = 64, bool MI16 = false, bool RING = false>
 static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1, int n_full = -1) {
     const int tiles_m = g.M / BM, tiles_n = g.N / BN;
     const int nblk = tiles_m * tiles_n;
@@ -808,12 +893,12 @@ static hipError_t launch_dma(const GemmArgs& g, hipStream_t s, int splits = 1, i
     else if (n_full < 0) n_full = 0;                    // every tile is cut along K
     const int n_tail = nblk - n_full;
     const dim3 grid(n_full + n_tail * splits), block(WM * WN * 64);
-    const size_t stages = (size_t)NS * (BM + BN) * BKT * 2;
+    const size_t stages = RING ? (size_t)5 * (BM + BN) * 32 * 2 : (size_t)NS * (BM + BN) * BKT * 2;
     const size_t epilogue = (size_t)WM * WN * 32 * (BN / WN + 8) * sizeof(float);
     const size_t smem = stages > epilogue ? stages : epilogue;
 #define BP_GEMM_LAUNCH(AR, BR)                                                                   \
     do {                                                                                         \
-        auto kern = gemm_dma_kernel<BM, BN, WM, WN, BKT, NS, AR, BR, MI16>;                         \
+        auto kern = gemm_dma_kernel<BM, BN, WM, WN, BKT, NS, AR, BR, MI16, RING>;                         \
         static std::atomic<bool> attr_set{false};   /* once per instantiation; host threads may race */ \
         if (smem > 64 * 1024 && !attr_set.load(std::memory_order_acquire)) {                                                     \
             hipError_t e = hipFuncSetAttribute((const void*)kern,                                \
@@ -917,6 +1002,10 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
         const long full = (t256 / ncu) * ncu, tail = t256 - full;
         const int splits =
             (g.split_ws && g.epi == EPI_NONE && tail < most) ? tail_splits(tail) : 1;
+        if (g.a_t && !g.b_t) {      // weight gradients: the five-slot ring
+            if (splits > 1) return launch_dma<256, 256, 2, 4, 5, 64, true, true>(g, s, splits, (int)full);
+            return launch_dma<256, 256, 2, 4, 5, 64, true, true>(g, s);
+        }
         if (splits > 1) return launch_dma<256, 256, 2, 4, 2, 64, true>(g, s, splits, (int)full);
         return launch_dma<256, 256, 2, 4, 2, 64, true>(g, s);
     }
@@ -936,7 +1025,10 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     // flop at the large-tile level (128 x 128 tiles are bound by the per-CU load path).
     if (t256 > 0 && g.split_ws && g.epi == EPI_NONE) {
         const int splits = tail_splits(t256);
-        if (splits > 1 && t256 * splits * 8 >= 5L * ncu) return launch_dma<256, 256, 2, 4, 2, 64, true>(g, s, splits, 0);
+        if (splits > 1 && t256 * splits * 8 >= 5L * ncu) {
+            if (g.a_t && !g.b_t) return launch_dma<256, 256, 2, 4, 5, 64, true, true>(g, s, splits, 0);
+            return launch_dma<256, 256, 2, 4, 2, 64, true>(g, s, splits, 0);
+        }
     }
     // Small outputs (128 x 128 tiles on fewer than three quarters of the CUs) with a long K: the same split, on the small
     // tiles (slices at least 1024 deep: below that the second kernel costs what the split gains)
