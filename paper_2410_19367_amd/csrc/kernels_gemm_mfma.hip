@@ -1003,11 +1003,16 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     const long t192 = (g.M % 256 == 0 && g.N % 192 == 0) ? (long)(g.M / 256) * (g.N / 192) : 0;
     // (the fused GELU-backward epilogue folds column sums over power-of-two lane groups: not 96 wide)
     // The 192-wide tile has fewer MFMAs per LDS read and per barrier: measured against the 256-wide
-    // one at equal fill it runs at about 0.85 of its rate with both operands read through the
-    // transpose path and a long contraction (weight gradients), else within 5 %.
-    const double rate192 = (g.a_t && !g.b_t && (long)g.K * g.nseg >= 4096) ? 0.85 : 0.95;
-    if (g.epi == EPI_NONE && t192 >= most && rate192 * fill(t192) > fill(t256))
+    // one at equal fill it runs at about 0.85 of its rate for weight gradients with a long contraction
+    // (both operands through the transpose path, no ring) and for the forward / data-gradient form
+    // (2048 x 6144 x 2048: 44.5 us against 46.0 us on three quarters of the CUs; 4096 x 15360 x 5120:
+    // 543 us against 494 us at a fill of 0.94), else within 5 %.
+    const bool nt = !g.a_t && g.b_t;
+    const double rate192 = ((g.a_t && !g.b_t && (long)g.K * g.nseg >= 4096) || nt) ? 0.85 : 0.95;
+    if (g.epi == EPI_NONE && t192 >= most && rate192 * fill(t192) > fill(t256)) {
+        if (nt) return launch_dma<256, 192, 2, 4, 2, 64, true>(g, s);
         return launch_dma<256, 192, 4, 2, 2>(g, s);
+    }
     // How many K slices the last, partly filled round of 256 x 256 tiles is cut into so that it fills
     // the chip too (at most 4, each at least 1024 deep so that the fp32 partials stay a small part of
     // the traffic; the slices need not be equal).  With fewer tiles than CUs this is plain split-K.
