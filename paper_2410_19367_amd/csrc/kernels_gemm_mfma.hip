@@ -564,10 +564,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(GemmArgs g, int t
         // the iteration after next reads first, into the first slot it has just freed; the second freed
         // slot is requested one k step later, in the next iteration's first step, and has a barrier
         // more to land: the barrier only ever waits for the older of the two requests, and the loads
-        // reach the CU's load path in two bursts per iteration instead of one.  Measured on the
+        // go out in two bursts per iteration instead of one.  Measured on the
         // weight-gradient shapes of the GPT-style stages: +13 % (2048 x 8192 x 16384: 1130 -> 1280
-        // TFLOP/s); with both operands contraction-major it is 2 % slower than two stages, so those
-        // keep them.
+        // TFLOP/s); with both operands contraction-major it is 2 % slower than two stages (a slot of 32
+        // along K is then half a cache line per row, and the requests to the L2 double), so those keep
+        // them.
         static_assert(!RING || (MI16 && BKT == 64 && NS == 5), "ring mode: 16x16x32 MFMAs, five slots of 32");
         constexpr int SLOT = (BM + BN) * 32 * 2;
         DmaPlan<BM, 32, NW, A_RMAJOR> ra;
@@ -1047,7 +1048,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
         return launch_dma<128, 128, 2, 4, 2>(g, s);
     }
     // Fewer tiles than that but a long K: 256 x 256 tiles on K slices keep the operand traffic per
-    // flop at the large-tile level (128 x 128 tiles are bound by the per-CU load path).
+    // flop at the large-tile level (128 x 128 tiles move twice the operand bytes per flop).
     if (t256 > 0 && g.split_ws && g.epi == EPI_NONE) {
         const int splits = tail_splits(t256);
         if (splits > 1 && t256 * splits * 8 >= 5L * ncu) {
