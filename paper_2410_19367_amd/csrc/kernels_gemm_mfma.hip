@@ -1036,14 +1036,19 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
     }
     // Too few 256 x 256 tiles to fill the chip.  Up to a contraction depth of 4096, 128 x 128 tiles
     // that do fill it win over large tiles cut along K: one launch, no fp32 partials (inside the
-    // BERT-style stage, 4096 x 1024 x 3072: 41.7 us against 48.6 us).  Deeper than that the small tiles
-    // lose: they move twice the operand bytes per flop, and inside a layer those come from HBM,
-    // not from a warm cache (2048 x 2048 x 8192: 96 us against 84 us; 2048 x 2560 x 10240: 229 against 115).
+    // BERT-style stage, 4096 x 1024 x 3072: 41.7 us against 48.6 us).  In the forward / data-gradient
+    // form, whose small-tile kernel runs three LDS stages, this holds up to a depth of 8192 when the
+    // small tiles fill whole rounds (inside the GPT-style stage, 2048 x 2048 x 8192: 72.7 us against
+    // 77.0 us with the partials; but 2048 x 2560 x 7680, 320 tiles on 256 CUs, loses).  Deeper than
+    // that, or with a partly filled round, the small tiles lose: they move twice the operand bytes
+    // per flop, and inside a layer those come from HBM, not from a warm cache (2048 x 2560 x 10240:
+    // 229 us against 115 us).
     // Not for weight gradients either: with both operands read through the transpose path the small
     // tiles lose more than the partials cost (2560 x 2560 x 16384: 334 us against 272 us).
     const long t128 = (long)(g.M / 128) * (g.N / 128);
-    if (t128 >= most && k_total <= 4096 && !(g.a_t && !g.b_t)) {
-        if (g.K % 128 == 0 && nt) return launch_dma<128, 128, 2, 4, 2, 128, true>(g, s);
+    const bool small_fill = t128 >= most && (k_total <= 4096 || (nt && k_total <= 8192 && fill(t128) >= 0.95));
+    if (small_fill && !(g.a_t && !g.b_t)) {
+        if (nt) return launch_dma<128, 128, 2, 4, 3, 64, true>(g, s);
         if (g.K % 128 == 0) return launch_dma<128, 128, 2, 4, 2, 128>(g, s);
         return launch_dma<128, 128, 2, 4, 2>(g, s);
     }
@@ -1063,15 +1068,17 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
         int splits = (int)(ncu / t128);
         if (splits > 4) splits = 4;
         while (splits > 1 && (k_total / splits < 1024 || (size_t)splits * g.M * g.N > g.split_ws_elems)) --splits;
-        if (splits > 1 && bk == 128 && nt) return launch_dma<128, 128, 2, 4, 2, 128, true>(g, s, splits, 0);
+        if (splits > 1 && nt) return launch_dma<128, 128, 2, 4, 3, 64, true>(g, s, splits, 0);
         if (splits > 1 && bk == 128) return launch_dma<128, 128, 2, 4, 2, 128>(g, s, splits, 0);
         if (splits > 1) return launch_dma<128, 128, 2, 4, 2>(g, s, splits, 0);
     }
-    // 8 waves (2 per SIMD) hide the LDS and load latencies better than 4 on these small tiles, and
-    // slices of 128 along K (two stages of 64 KB) halve the number of barriers per MFMA
-    // (forward / data-gradient form: 16x16x32 MFMAs and loads first, as on the large tiles: 2048^3
-    // 21.9 us against 23.3 us)
-    if (g.K % 128 == 0 && nt) return launch_dma<128, 128, 2, 4, 2, 128, true>(g, s);
+    // 8 waves (2 per SIMD) hide the LDS and load latencies better than 4 on these small tiles.
+    // Forward / data-gradient form: 16x16x32 MFMAs and loads first, as on the large tiles, and three
+    // stages of 64 along K (96 KB), so that a slice has two barriers to land (against two stages of
+    // 128: 2048^3 20.7 us against 21.9 us, 2048 x 2048 x 8192 63.7 us against 67.9 us, 1024 x 1024 x
+    // 4096 27.9 us against 31.8 us).  The other forms: slices of 128 along K (two stages of 64 KB),
+    // which halve the number of barriers per MFMA.
+    if (nt) return launch_dma<128, 128, 2, 4, 3, 64, true>(g, s);
     if (g.K % 128 == 0) return launch_dma<128, 128, 2, 4, 2, 128>(g, s);
     return launch_dma<128, 128, 2, 4, 2>(g, s);
 }
