@@ -1,9 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the stage forward+backward hot path on one MI355X.
 
-One step = one pass of the whole hot path over one batch of the workload: for each of the
-config's micro-batches, the chunk's forward then its backward (weight gradients accumulated in
-fp32 across the micro-batches); for the V-schedule workload one whole BitPipe iteration.  Inputs
+One step = one pass of the whole hot path over one batch of the workload: the chunk's forward and
+backward for each of the config's micro-batches (weight gradients accumulated in fp32 across the
+micro-batches), called as F(0) F(1) B(0) F(2) B(1) ... with the forwards on a stream of their own
+(bp_opts.forward_ahead; `--plain-order`, and the widest workload by itself: F(0) B(0) F(1) B(1) ...
+on one stream; `config.call_order` says which); for the V-schedule workload one whole BitPipe
+iteration.  Inputs
 are synthetic (seeded N(0,1) activations and upstream gradients, N(0,0.02) weights) and resident
 in HBM before the timed region.
 
@@ -121,10 +124,15 @@ def bench_stage(args, cfg, bp, si, torch, np, steps, warmup):
             return torch.from_numpy(si.to_bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
         return torch.from_numpy(a).cuda()
 
+    # Forwards one micro-batch ahead on their own stream fill the CUs that the start and the end of
+    # every kernel leave idle: worth 5-12 % where kernels are short (cfg1, cfg2, cfg5, cfg6).  At
+    # cfg3's size (single GEMMs of 0.5-3 ms) there is nothing to fill and two large GEMMs side by
+    # side only disturb each other's L2 working sets (-2 %), so wide layers keep the plain order.
+    plain = args.plain_order or 2.0 * cfg.T * cfg.hidden * cfg.F > 3e11
     st = bp.bp_stage_init_ex(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, cfg.microbatch, cfg.causal,
                              n_chunks=1, mlp=cfg.mlp, dtype=bp.BP_BF16 if cfg.dtype == "bf16" else bp.BP_F32,
                              max_inflight=2, ln_eps=cfg.ln_eps, stash_recompute=int(args.stash_recompute),
-                             wgrad_group=args.wgrad_group)
+                             wgrad_group=args.wgrad_group, forward_ahead=int(not plain))
     params = si.make_params(cfg, bulk=True)
     for l in range(cfg.layers):
         for name, tid in bp.TENSOR_IDS.items():
@@ -140,11 +148,23 @@ def bench_stage(args, cfg, bp, si, torch, np, steps, warmup):
     out = torch.empty_like(acts[0])
     gin = torch.empty_like(acts[0])
 
+    outs = [out, torch.empty_like(out)]
+
     def step():
         bp.bp_stage_zero_grad(st)
+        if plain:                   # F(0) B(0) F(1) B(1) ..., everything on the stage's stream
+            for mb in range(cfg.n_micro):
+                bp.bp_stage_forward(st, 0, mb, acts[mb], out)
+                bp.bp_stage_backward(st, 0, mb, gouts[mb], gin)
+            return
+        # F(0) F(1) B(0) F(2) B(1) ...: the stage always has the next forward at hand, as in the
+        # steady state of the schedule, and runs it beside the backward of the micro-batch before
+        bp.bp_stage_forward(st, 0, 0, acts[0], outs[0])
         for mb in range(cfg.n_micro):
-            bp.bp_stage_forward(st, 0, mb, acts[mb], out)
+            if mb + 1 < cfg.n_micro:
+                bp.bp_stage_forward(st, 0, mb + 1, acts[mb + 1], outs[(mb + 1) & 1])
             bp.bp_stage_backward(st, 0, mb, gouts[mb], gin)
+        bp.bp_stage_wait_forward(st)
 
     bp.bp_stage_reset_peak_bytes(st)
     dt, per = _time_steps(torch, step, steps, warmup)
@@ -197,7 +217,9 @@ def bench_stage(args, cfg, bp, si, torch, np, steps, warmup):
         "dtype": cfg.dtype,
         "config": {"workload": cfg.name, "layers": cfg.layers, "hidden": cfg.hidden, "heads": cfg.heads,
                    "mlp": cfg.F, "seq": cfg.seq, "microbatch": cfg.microbatch, "causal": cfg.causal,
-                   "micro_batches_per_step": cfg.n_micro},
+                   "micro_batches_per_step": cfg.n_micro,
+                   "call_order": "F(0) B(0) F(1) B(1) ..., one stream" if plain else
+                                 "F(0) F(1) B(0) F(2) B(1) ..., forwards on their own stream"},
         "tokens_per_s": round(tokens_step * steps / dt, 1),
         "ms_per_microbatch": round(dt / steps / cfg.n_micro * 1e3, 4),
         "mfma_util": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -330,6 +352,9 @@ def main():
     ap.add_argument("--wgrad-group", type=int, default=0,
                     help="micro-batches per grouped weight-gradient GEMM (0: the library's default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plain-order", action="store_true",
+                    help="stage workloads: forward and backward of a micro-batch back to back on one stream "
+                         "(default: forwards one micro-batch ahead on their own stream, bp_opts.forward_ahead)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()

@@ -81,6 +81,18 @@ typedef struct bp_opts {
                            LayerNorm outputs and the GELU output are not kept (10*T*H per layer)
                            and are recomputed from x, y, u right before the weight-gradient GEMMs
                            that read them: the activation-memory axis of Table 2               */
+    int forward_ahead;  /* 1: bp_stage_forward runs on a stream of the object's own, behind everything
+                           the stage's stream holds at the moment of the call, and beside what is
+                           enqueued there later: called in the order F(0) F(1) B(0) F(2) B(1) ...
+                           (the steady state of the schedules of Section 3, where a device always
+                           has the next forward at hand), the forward of one micro-batch overlaps
+                           the backward of the one before, filling the CUs that the start and the
+                           end of every kernel leave idle.  Results are the same bit for bit.
+                           act_out (and act_in, which the forward still reads) belong to the call
+                           until the stage's stream has been made to wait for it:
+                           bp_stage_wait_forward, the backward of the same micro-batch,
+                           bp_stage_get_grad and bp_stage_destroy do that.  0: forwards run on the
+                           stage's stream like everything else.  bp_run_schedule ignores it.     */
 } bp_opts;
 
 /* Create a stage object holding one chunk of `layers` pre-LN transformer layers in bf16 with
@@ -160,6 +172,11 @@ int bp_stage_backward_dir(bp_stage_t* st, int chunk, int mb, const void* grad_ou
  * Completes the weight-gradient groups still open first.  Asynchronous (enqueued on the object's
  * streams; bp_stage_get_grad synchronises).  Calling it twice in a row adds nothing the second time. */
 int bp_stage_merge_directions(bp_stage_t* st);
+
+/* With bp_opts.forward_ahead: make the stage's stream wait for every forward enqueued so far, so
+ * that work enqueued on it afterwards (the caller's consumer of act_out, a copy to the next stage)
+ * sees their outputs.  Asynchronous; without forward_ahead it does nothing.  Errors: BP_EINVAL, BP_EHIP. */
+int bp_stage_wait_forward(bp_stage_t* st);
 
 /* One operation of a schedule: forward or backward of global stage `stage` (= chunk index) on
  * micro-batch `mb`, in pipeline `dir`, placed on virtual device `vdev`. */

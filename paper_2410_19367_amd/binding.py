@@ -24,7 +24,7 @@ KERNEL_IDS = {n: i for i, n in enumerate(
 # every symbol include/bitpipe_stage.h declares
 EXPORTS = (
     "bp_stage_init", "bp_stage_init_ex", "bp_stage_stash_bytes", "bp_stage_held_bytes", "bp_stage_reset_peak_bytes", "bp_stage_destroy", "bp_stage_set_param",
-    "bp_stage_get_grad", "bp_stage_zero_grad", "bp_stage_merge_directions", "bp_stage_set_seqlens", "bp_stage_forward",
+    "bp_stage_get_grad", "bp_stage_zero_grad", "bp_stage_merge_directions", "bp_stage_wait_forward", "bp_stage_set_seqlens", "bp_stage_forward",
     "bp_stage_backward", "bp_stage_backward_dir", "bp_schedule_vmap", "bp_schedule_generate",
     "bp_schedule_validate", "bp_schedule_simulate", "bp_run_schedule", "bp_schedule_vmap_ex",
     "bp_schedule_generate_ex", "bp_schedule_validate_ex", "bp_schedule_simulate_ex", "bp_run_schedule_ex",
@@ -39,7 +39,7 @@ EXPORTS = (
 class bp_opts(C.Structure):
     _fields_ = [("n_chunks", C.c_int), ("mlp", C.c_int), ("dtype", C.c_int),
                 ("max_inflight", C.c_int), ("ln_eps", C.c_float), ("hip_stream", C.c_void_p),
-                ("wgrad_group", C.c_int), ("stash_recompute", C.c_int)]
+                ("wgrad_group", C.c_int), ("stash_recompute", C.c_int), ("forward_ahead", C.c_int)]
 
 
 class bp_layout(C.Structure):
@@ -81,6 +81,7 @@ def lib():
         l.bp_stage_get_grad.argtypes = [vp, ci, ci, ci, vp, C.c_size_t]
         l.bp_stage_zero_grad.argtypes = [vp]
         l.bp_stage_merge_directions.argtypes = [vp]
+        l.bp_stage_wait_forward.argtypes = [vp]
         l.bp_stage_set_seqlens.argtypes = [vp, ci, vp]
         l.bp_stage_forward.argtypes = [vp, ci, ci, vp, vp]
         l.bp_stage_backward.argtypes = [vp, ci, ci, vp, vp]
@@ -158,9 +159,10 @@ def bp_stage_init(layers, hidden, heads, seq, microbatch, causal):
 
 def bp_stage_init_ex(layers, hidden, heads, seq, microbatch, causal, n_chunks=0, mlp=0,
                      dtype=BP_BF16, max_inflight=0, ln_eps=0.0, hip_stream=None, wgrad_group=0,
-                     stash_recompute=0):
+                     stash_recompute=0, forward_ahead=0):
     h = C.c_void_p()
-    o = bp_opts(n_chunks, mlp, dtype, max_inflight, ln_eps, hip_stream, wgrad_group, stash_recompute)
+    o = bp_opts(n_chunks, mlp, dtype, max_inflight, ln_eps, hip_stream, wgrad_group, stash_recompute,
+                forward_ahead)
     _check(lib().bp_stage_init_ex(C.byref(h), layers, hidden, heads, seq, microbatch, int(causal),
                                   C.byref(o)))
     return h
@@ -201,6 +203,10 @@ def bp_stage_zero_grad(st):
 
 def bp_stage_merge_directions(st):
     return _check(lib().bp_stage_merge_directions(st))
+
+
+def bp_stage_wait_forward(st):
+    return _check(lib().bp_stage_wait_forward(st))
 
 
 def bp_stage_set_seqlens(st, mb, lens):

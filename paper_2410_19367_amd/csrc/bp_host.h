@@ -51,6 +51,8 @@ struct StashSlot {
     int chunk = -1, mb = -1;
     hipEvent_t side_done = nullptr;   // last side-stream reader of this slot (null: none pending)
     bool side_pending = false;
+    hipEvent_t fwd_done = nullptr;    // end of the forward that filled this slot, on the forward stream
+    bool fwd_pending = false;
     bool held = false;     // backward done, but the weight gradients of its group are still to come
 };
 
@@ -93,6 +95,12 @@ struct LaneState {
     size_t ws_splitk_elems = 0;
     float* ws_splitk_side = nullptr;     // the same for the weight-gradient GEMMs of the side stream
     size_t ws_splitk_side_elems = 0;
+    // bp_opts.forward_ahead: forwards run on a stream of their own, so that the forward of one
+    // micro-batch overlaps the backward of another; it has its own split-K workspace
+    hipStream_t fstream = nullptr;
+    hipEvent_t ev_call = nullptr;        // main -> forward stream: everything enqueued before a forward call
+    hipEvent_t ev_fwd_all = nullptr;     // forward stream -> main: every forward enqueued so far
+    float* ws_splitk_fwd = nullptr;
 };
 
 struct Stage : LaneState {
@@ -103,6 +111,7 @@ struct Stage : LaneState {
     size_t esz = 2;
     float eps = 1e-5f;
     bool overlap = true;                 // false: everything on `stream` (also while timing kernels)
+    bool forward_ahead = false;          // forwards on `fstream`
 
     // parameters (matrices in the storage dtype, vectors fp32) and fp32 gradients per direction
     void* params = nullptr;
@@ -193,6 +202,8 @@ struct Stage : LaneState {
              int M, int N, int K, const float* bias, const void* residual, int accumulate,
              hipStream_t on = nullptr, bool use_on = false);
     hipStream_t side_stream() const { return (overlap && !prof.on && side) ? side : stream; }
+    hipStream_t forward_stream() const { return (forward_ahead && !prof.on && fstream) ? fstream : stream; }
+    int wait_forward();
     int sync_all();
     int forward(int chunk, int mb, const void* act_in, void* act_out);
     int backward(int chunk, int mb, const void* grad_out, void* grad_in, int dir);

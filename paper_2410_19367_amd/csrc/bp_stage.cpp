@@ -144,6 +144,8 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
         return fail(BP_EINVAL, "stash_recompute %d is not 0 or 1", opt.stash_recompute);
     if (opt.wgrad_group < 0 || opt.wgrad_group > kMaxGemmSegments)
         return fail(BP_EINVAL, "wgrad_group %d outside 0..%d", opt.wgrad_group, kMaxGemmSegments);
+    if (opt.forward_ahead != 0 && opt.forward_ahead != 1)
+        return fail(BP_EINVAL, "forward_ahead %d is not 0 or 1", opt.forward_ahead);
     if (opt.mlp % 8) return fail(BP_ESHAPE, "mlp width must be a multiple of 8");
     if ((size_t)seq * sizeof(float) * 2 > 56000)
         return fail(BP_ESHAPE, "seq %d too long for the attention kernels", seq);
@@ -208,6 +210,18 @@ int Stage::create(Stage** out, int layers, int hidden, int heads, int seq, int m
     // lane 0: workspaces, the second stream (default priority, not synchronising with the null
     // stream) and the events that order the two
     if ((rc = st->lane_alloc(*st, false))) { delete st; return rc; }
+    if (opt.forward_ahead) {    // the forward stream, its two events and its split-K workspace
+        hipError_t fe = hipStreamCreateWithFlags(&st->fstream, hipStreamNonBlocking);
+        if (fe == hipSuccess) fe = hipEventCreateWithFlags(&st->ev_call, hipEventDisableTiming);
+        if (fe == hipSuccess) fe = hipEventCreateWithFlags(&st->ev_fwd_all, hipEventDisableTiming);
+        if (fe != hipSuccess) {
+            delete st;
+            return fail(BP_EHIP, "creating the forward stream failed: %s", hipGetErrorString(fe));
+        }
+        if (st->ws_splitk_elems &&
+            (rc = dev_alloc((void**)&st->ws_splitk_fwd, st->ws_splitk_elems * sizeof(float)))) { delete st; return rc; }
+        st->forward_ahead = true;
+    }
 
     // initial values: zeros, LN gamma = 1
     hipError_t e = hipMemsetAsync(st->params, 0, n_layers * poff, st->stream);
@@ -273,6 +287,10 @@ int Stage::lane_alloc(LaneState& ln, bool with_stream) {
 void Stage::lane_free(LaneState& ln, bool with_stream) {
     if (ln.side) { hipStreamSynchronize(ln.side); hipStreamDestroy(ln.side); }
     if (with_stream && ln.stream) { hipStreamSynchronize(ln.stream); hipStreamDestroy(ln.stream); }
+    if (ln.fstream) { hipStreamSynchronize(ln.fstream); hipStreamDestroy(ln.fstream); }
+    if (ln.ev_call) hipEventDestroy(ln.ev_call);
+    if (ln.ev_fwd_all) hipEventDestroy(ln.ev_fwd_all);
+    hipFree(ln.ws_splitk_fwd);
     for (auto e : ln.ev_ready) if (e) hipEventDestroy(e);
     for (auto e : ln.ev_layer_done) if (e) hipEventDestroy(e);
     if (ln.ev_misc) hipEventDestroy(ln.ev_misc);
@@ -321,6 +339,7 @@ int Stage::make_view(Stage** out) {
 int Stage::sync_all() {
     hipError_t e = hipStreamSynchronize(stream);
     if (e == hipSuccess && side) e = hipStreamSynchronize(side);
+    if (e == hipSuccess && fstream) e = hipStreamSynchronize(fstream);
     if (e != hipSuccess) return fail(BP_EHIP, "synchronise: %s", hipGetErrorString(e));
     for (Stage* v : views) {
         int rc = v->sync_all();
@@ -342,6 +361,7 @@ Stage::~Stage() {
     for (auto& s : slots) {
         hipFree(s.buf);
         if (s.side_done) hipEventDestroy(s.side_done);
+        if (s.fwd_done) hipEventDestroy(s.fwd_done);
     }
     for (int dir = 0; dir < 2; ++dir)
         for (auto& grp : pend[dir])
@@ -379,6 +399,7 @@ int Stage::set_param(int chunk, int layer, int id, const float* host, size_t n) 
     int rc = check_tensor(chunk, layer, id, n);
     if (rc) return rc;
     if (!host) return fail(BP_EINVAL, "host pointer is null");
+    if ((rc = wait_forward())) return rc;    // a forward still in flight reads the old values
     void* dst = param(chunk, layer, id);
     hipError_t e;
     // rows x cols of the [in, out] matrix
@@ -604,6 +625,7 @@ int Stage::set_seqlens(int mb, const int32_t* host) {
         if (rc) return rc;
         lens[mb] = dev;
     }
+    if (int rc = wait_forward()) return rc;  // a forward still in flight reads the old lengths
     hipError_t e = hipMemcpyAsync(dev, host, B * sizeof(int32_t), hipMemcpyHostToDevice, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail(BP_EHIP, "set_seqlens: %s", hipGetErrorString(e));
@@ -655,7 +677,7 @@ int Stage::acquire_slot(int chunk, int mb, int* out) {
     }
     if (sl.side_pending) {
         // the previous owner's weight-gradient kernels may still be reading this stash
-        hipError_t e = hipStreamWaitEvent(stream, sl.side_done, 0);
+        hipError_t e = hipStreamWaitEvent(forward_stream(), sl.side_done, 0);
         if (e != hipSuccess) return fail(BP_EHIP, "stash reuse wait: %s", hipGetErrorString(e));
         sl.side_pending = false;
     }
@@ -680,8 +702,11 @@ int Stage::gemm(const void* A, int lda, int a_t, const void* Bm, int ldb, int b_
     g.A = A; g.B = Bm; g.C = C; g.bias = bias; g.residual = residual;
     g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
     g.a_t = a_t; g.b_t = b_t; g.accumulate = accumulate;
-    if (!use_on || on == stream) {      // the split-K workspace belongs to the main stream
+    if (!use_on || on == stream) {      // one split-K workspace per stream: the main stream's ...
         g.split_ws = ws_splitk;
+        g.split_ws_elems = ws_splitk_elems;
+    } else if (on == fstream && ws_splitk_fwd) {    // ... and the forward stream's
+        g.split_ws = ws_splitk_fwd;
         g.split_ws_elems = ws_splitk_elems;
     }
     prof.tag_gemm(M, N, K, a_t, b_t, 1, 0);
@@ -696,6 +721,14 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
     if (!act_in || !act_out) return fail(BP_EINVAL, "activation pointer is null");
     if (act_in == act_out) return fail(BP_EINVAL, "act_in and act_out must not overlap");
     int slot, rc;
+    // With forward_ahead the call runs on the forward stream, behind everything the stage's stream
+    // holds at this moment (the caller's producer of act_in, parameter updates, earlier calls);
+    // backwards enqueued later run beside it.
+    const hipStream_t fs = forward_stream();
+    if (fs != stream) {
+        BP_LAUNCH(hipEventRecord(ev_call, stream));
+        BP_LAUNCH(hipStreamWaitEvent(fs, ev_call, 0));
+    }
     if ((rc = acquire_slot(chunk, mb, &slot))) return rc;
     note_held();
     auto it = lens.find(mb);
@@ -716,23 +749,23 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
             BP_LAUNCH(launch_ln_fwd(dtype, T, H, x, (const float*)param(chunk, l, BP_LN1_G),
                                     (const float*)param(chunk, l, BP_LN1_B), eps, a_out,
                                     (float*)(sb + s_mean1), (float*)(sb + s_rstd1),
-                                    l == 0 ? sb + s_x : nullptr, stream));
+                                    l == 0 ? sb + s_x : nullptr, fs));
         }
         if ((rc = gemm(a_out, H, 0, param_t(chunk, l, BP_WQKV), H, 1, sb + s_qkv, 3 * H, T, 3 * H, H,
-                       (const float*)param(chunk, l, BP_BQKV), nullptr, 0))) return rc;
+                       (const float*)param(chunk, l, BP_BQKV), nullptr, 0, fs, true))) return rc;
         {
             AttnArgs a{B, S, heads, d, causal ? 1 : 0, ln, sb + s_qkv, sb + s_ctx, (float*)(sb + s_lse),
                        nullptr, nullptr, nullptr};
             Scoped sc(this, BP_K_ATTN_FWD, 4.0 * T * S * H * attn_c, 0);
-            BP_LAUNCH(launch_attn_fwd(dtype, a, stream));
+            BP_LAUNCH(launch_attn_fwd(dtype, a, fs));
         }
         if ((rc = gemm(sb + s_ctx, H, 0, param_t(chunk, l, BP_WO), H, 1, sb + s_y, H, T, H, H,
-                       (const float*)param(chunk, l, BP_BO), x, 0))) return rc;
+                       (const float*)param(chunk, l, BP_BO), x, 0, fs, true))) return rc;
         {
             Scoped sc(this, BP_K_LN_FWD, 0, 2 * unit);
             BP_LAUNCH(launch_ln_fwd(dtype, T, H, sb + s_y, (const float*)param(chunk, l, BP_LN2_G),
                                     (const float*)param(chunk, l, BP_LN2_B), eps, m_out,
-                                    (float*)(sb + s_mean2), (float*)(sb + s_rstd2), nullptr, stream));
+                                    (float*)(sb + s_mean2), (float*)(sb + s_rstd2), nullptr, fs));
         }
         {   // u = m W1 and g = gelu(u + b1): one kernel when the GEMM can carry the activation
             GemmArgs fg;
@@ -744,18 +777,34 @@ int Stage::forward(int chunk, int mb, const void* act_in, void* act_out) {
             if (fuse_gelu && gemm_can_fuse_epilogue(dtype, fg)) {
                 prof.tag_gemm(T, F, H, 0, 1, 1, EPI_GELU_FWD);
                 Scoped sc(this, BP_K_GEMM, 2.0 * T * (double)F * H, 0);
-                BP_LAUNCH(launch_gemm(dtype, fg, stream));
+                BP_LAUNCH(launch_gemm(dtype, fg, fs));
             } else {
                 if ((rc = gemm(m_out, H, 0, param_t(chunk, l, BP_W1), H, 1, sb + s_u, F, T, F, H, nullptr,
-                               nullptr, 0))) return rc;
+                               nullptr, 0, fs, true))) return rc;
                 Scoped sc(this, BP_K_GELU_FWD, 0, 2.0 * T * F * esz);
                 BP_LAUNCH(launch_gelu_fwd(dtype, T, F, sb + s_u, (const float*)param(chunk, l, BP_B1),
-                                          g_out, stream));
+                                          g_out, fs));
             }
         }
         if ((rc = gemm(g_out, F, 0, param_t(chunk, l, BP_W2), F, 1, z, H, T, H, F,
-                       (const float*)param(chunk, l, BP_B2), sb + s_y, 0))) return rc;
+                       (const float*)param(chunk, l, BP_B2), sb + s_y, 0, fs, true))) return rc;
     }
+    if (fs != stream) {     // the backward of this micro-batch (on the stage's stream) waits for this
+        StashSlot& sl = slots[slot];
+        if (!sl.fwd_done) BP_LAUNCH(hipEventCreateWithFlags(&sl.fwd_done, hipEventDisableTiming));
+        BP_LAUNCH(hipEventRecord(sl.fwd_done, fs));
+        sl.fwd_pending = true;
+    }
+    return BP_OK;
+}
+
+// The stage's stream waits for every forward enqueued so far (forward_ahead; a no-op otherwise).
+int Stage::wait_forward() {
+    if (!fstream) return BP_OK;
+    hipError_t e = hipEventRecord(ev_fwd_all, fstream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(stream, ev_fwd_all, 0);
+    if (e != hipSuccess) return fail(BP_EHIP, "wait for the forward stream: %s", hipGetErrorString(e));
+    for (auto& sl : slots) sl.fwd_pending = false;
     return BP_OK;
 }
 
@@ -788,6 +837,10 @@ int Stage::backward(int chunk, int mb, const void* grad_out, void* grad_in, int 
         return e != hipSuccess ? e : hipStreamWaitEvent(ss, ev_ready[k], 0);
     };
 
+    if (slots[slot].fwd_pending) {      // the forward that filled the stash ran on the forward stream
+        BP_HIP(hipStreamWaitEvent(stream, slots[slot].fwd_done, 0));
+        slots[slot].fwd_pending = false;
+    }
     if (two && call_done_pending) {
         // the workspaces are shared by all calls: the previous backward's side work must be over
         BP_HIP(hipStreamWaitEvent(stream, ev_misc, 0));
@@ -1025,6 +1078,11 @@ int bp_stage_zero_grad(bp_stage_t* st) {
     BP_ST(st);
     return s_->zero_grad();
 }
+int bp_stage_wait_forward(bp_stage_t* st) {
+    if (!st) return fail(BP_EINVAL, "stage is null");
+    return ((Stage*)st)->wait_forward();
+}
+
 int bp_stage_merge_directions(bp_stage_t* st) {
     BP_ST(st);
     return s_->merge_directions();

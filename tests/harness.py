@@ -46,7 +46,7 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 class GpuStage:
     """Drives one library stage object for a StageConfig."""
 
-    def __init__(self, cfg: si.StageConfig, max_inflight=0, wgrad_group=0, stash_recompute=0):
+    def __init__(self, cfg: si.StageConfig, max_inflight=0, wgrad_group=0, stash_recompute=0, forward_ahead=0):
         import paper_2410_19367_amd as bp
         self.bp = bp
         self.cfg = cfg
@@ -54,7 +54,8 @@ class GpuStage:
                                      cfg.causal, n_chunks=cfg.n_chunks, mlp=cfg.mlp,
                                      dtype=bp.BP_BF16 if cfg.dtype == "bf16" else bp.BP_F32,
                                      max_inflight=max_inflight, ln_eps=cfg.ln_eps,
-                                     wgrad_group=wgrad_group, stash_recompute=stash_recompute)
+                                     wgrad_group=wgrad_group, stash_recompute=stash_recompute,
+                                     forward_ahead=forward_ahead)
 
     def close(self):
         if self.h is not None:
@@ -100,18 +101,23 @@ def make_oracle(cfg: si.StageConfig, params):
 
 
 def run_fwd_bwd_parity(cfg: si.StageConfig, n_micro=None, seed=0, ln_jitter=0.0, check=True, wgrad_group=0,
-                       stash_recompute=0, sync_each=True, grad_layers=None):
+                       stash_recompute=0, sync_each=True, grad_layers=None, forward_ahead=False):
     """F then B for each micro-batch on both sides; returns dict name -> rel err.
     sync_each=False: the GPU side runs all its micro-batches back to back with no device
     synchronisation in between (the call pattern bench.py times: consecutive calls overlap on the
     library's two streams); its outputs are kept on the device and compared afterwards.
-    grad_layers: layers whose parameter gradients are compared (default: all)."""
+    grad_layers: layers whose parameter gradients are compared (default: all).
+    forward_ahead (with sync_each=False): the object runs its forwards on a stream of their own and
+    the calls come in the order F(0) F(1) B(0) F(2) B(1) ..., so that the forward of one micro-batch
+    overlaps the backward of the one before."""
+    assert not (forward_ahead and sync_each)
     torch = torch_mod()
     n_micro = cfg.n_micro if n_micro is None else n_micro
     params = si.make_params(cfg, seed, ln_jitter)
     orc = make_oracle(cfg, params)
     errs = {}
-    with GpuStage(cfg, wgrad_group=wgrad_group, stash_recompute=stash_recompute) as g:
+    with GpuStage(cfg, wgrad_group=wgrad_group, stash_recompute=stash_recompute,
+                  forward_ahead=int(forward_ahead)) as g:
         g.load_params(params)
         g.bp.bp_stage_zero_grad(g.h)
         kept = []
@@ -124,10 +130,18 @@ def run_fwd_bwd_parity(cfg: si.StageConfig, n_micro=None, seed=0, ln_jitter=0.0,
                 ins.append((to_dev(si.make_activation(cfg, "act_in", mb, seed), cfg.dtype),
                             to_dev(si.make_activation(cfg, "grad_out", mb, seed), cfg.dtype)))
             torch.cuda.synchronize()
-            for mb in range(n_micro):
-                z = g.forward(0, mb, ins[mb][0])
-                dx = g.backward(0, mb, ins[mb][1])
-                kept.append((z, dx))
+            if forward_ahead:
+                zs = [g.forward(0, 0, ins[0][0])]
+                for mb in range(n_micro):
+                    if mb + 1 < n_micro:
+                        zs.append(g.forward(0, mb + 1, ins[mb + 1][0]))
+                    kept.append((zs[mb], g.backward(0, mb, ins[mb][1])))
+                g.bp.bp_stage_wait_forward(g.h)
+            else:
+                for mb in range(n_micro):
+                    z = g.forward(0, mb, ins[mb][0])
+                    dx = g.backward(0, mb, ins[mb][1])
+                    kept.append((z, dx))
             torch.cuda.synchronize()
         for mb in range(n_micro):
             x = si.make_activation(cfg, "act_in", mb, seed)

@@ -1,9 +1,11 @@
 """GPU parity at the baseline's full shapes, in the launch configuration bench.py times.
 
 What runs at full size against the oracle (fp64 numpy, tens of seconds per micro-batch):
-  * cfg1: all 8 micro-batches back to back with no synchronisation in between and the library's
-    default weight-gradient group (8), so the grouped weight-gradient GEMMs (8 contraction
-    segments, 16384 tokens, on the second stream) are compared at the shape the bench times;
+  * cfg1: all 8 micro-batches back to back with no synchronisation in between, forwards one
+    micro-batch ahead on their own stream (bp_opts.forward_ahead) and the library's default
+    weight-gradient group (8), so the grouped weight-gradient GEMMs (8 contraction segments, 16384
+    tokens, on the second stream) are compared at the shape, and in the call pattern, the bench
+    times; plus a check that the same calls without forward_ahead give the same bits;
   * cfg2: 4 of its 8 micro-batches, which completes one default group (4) the same way;
   * cfg3: one micro-batch through both layers against the oracle (the group is flushed by the
     gradient read), plus a self-consistency check on the GPU that 4 micro-batches grouped by 4
@@ -33,8 +35,54 @@ def test_cfg1_gpt_h2048_all_microbatches_default_group():
     """4 layers, H 2048, 16 heads, S 2048, B 1, causal: the bench's step, i.e. all 8 micro-batches
     forward+backward without a device synchronisation in between, weight gradients in one group of
     8 (the library's default at T = 2048), against the oracle's fp64 sum over the micro-batches."""
-    errs = hz.run_fwd_bwd_parity(si.CONFIGS[1], n_micro=8, sync_each=False)
+    errs = hz.run_fwd_bwd_parity(si.CONFIGS[1], n_micro=8, sync_each=False, forward_ahead=True)
     _report("cfg1", errs)
+
+
+def _all_bits(cfg, n_micro, forward_ahead):
+    import torch
+    params = si.make_params(cfg, 0, 0.0)
+    ins = [(hz.to_dev(si.make_activation(cfg, "act_in", mb, 0), cfg.dtype),
+            hz.to_dev(si.make_activation(cfg, "grad_out", mb, 0), cfg.dtype)) for mb in range(n_micro)]
+    with hz.GpuStage(cfg, max_inflight=2, forward_ahead=int(forward_ahead)) as g:
+        g.load_params(params)
+        for mb in range(n_micro):
+            lens = si.make_seqlens(cfg, mb, 0)
+            if lens is not None:
+                g.bp.bp_stage_set_seqlens(g.h, mb, lens)
+        outs = []
+        for rep in range(2):        # the second iteration reuses stash slots filled by the first
+            g.bp.bp_stage_zero_grad(g.h)
+            outs = []
+            if forward_ahead:
+                zs = [g.forward(0, 0, ins[0][0])]
+                for mb in range(n_micro):
+                    if mb + 1 < n_micro:
+                        zs.append(g.forward(0, mb + 1, ins[mb + 1][0]))
+                    outs.append((zs[mb], g.backward(0, mb, ins[mb][1])))
+                g.bp.bp_stage_wait_forward(g.h)
+            else:
+                for mb in range(n_micro):
+                    z = g.forward(0, mb, ins[mb][0])
+                    outs.append((z, g.backward(0, mb, ins[mb][1])))
+        torch.cuda.synchronize()
+        grads = {(l, n): g.grad(0, l, n) for l in range(cfg.layers) for n in si.PARAM_NAMES}
+        return [(hz.to_host(z), hz.to_host(dx)) for z, dx in outs], grads
+
+
+@pytest.mark.parametrize("idx,n_micro", [(1, 8), (2, 4)])
+def test_forward_ahead_gives_the_same_bits(idx, n_micro):
+    """Self-consistency on the GPU at full shape: the step with forwards one micro-batch ahead on their
+    own stream (two iterations, so that stash slots are reused across the streams) against the same
+    calls in the plain order on one stream.  Same kernels, same order of additions: equal bits."""
+    cfg = si.CONFIGS[idx]
+    outs_a, grads_a = _all_bits(cfg, n_micro, True)
+    outs_b, grads_b = _all_bits(cfg, n_micro, False)
+    for mb, ((za, dxa), (zb, dxb)) in enumerate(zip(outs_a, outs_b)):
+        assert np.array_equal(za, zb), f"act_out[{mb}] differs"
+        assert np.array_equal(dxa, dxb), f"grad_in[{mb}] differs"
+    for key in grads_a:
+        assert np.array_equal(grads_a[key], grads_b[key]), f"grad {key} differs"
 
 
 def test_cfg2_bert_h1024_padded_one_full_group():

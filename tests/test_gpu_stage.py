@@ -31,6 +31,20 @@ def test_small_bf16_stages(name, kw):
     print(name, "worst", worst)
 
 
+@pytest.mark.parametrize("stash_recompute,wgrad_group,causal", [(0, 0, True), (1, 2, True), (0, 3, False)])
+def test_forward_ahead_small_stages(stash_recompute, wgrad_group, causal):
+    """Forwards on their own stream, one micro-batch ahead of the backwards (F0 F1 B0 F2 B1 ...), no
+    synchronisation in between: outputs, input gradients and accumulated parameter gradients against
+    the oracle, with the full and the reduced stash and with weight-gradient groups that end inside
+    and at the end of the run."""
+    kw = dict(layers=2, hidden=256, heads=4, seq=192, microbatch=2, causal=causal)
+    if not causal:
+        kw.update(len_lo=40, len_hi=192)
+    cfg = si.scaled(si.CONFIGS[1], name="small_ahead", n_micro=5, **kw)
+    hz.run_fwd_bwd_parity(cfg, ln_jitter=0.1, sync_each=False, forward_ahead=True,
+                          stash_recompute=stash_recompute, wgrad_group=wgrad_group)
+
+
 def test_small_fp32_bert_padded():
     cfg = si.scaled(si.CONFIGS[0], name="small_f32_bert", causal=False, len_lo=10, len_hi=64,
                     microbatch=3, n_micro=2)
