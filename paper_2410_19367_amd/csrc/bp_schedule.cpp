@@ -417,6 +417,14 @@ int Stage::run_schedule(const Layout& L, const bp_op* order, int n_ops, int D, c
     int rc = schedule_validate(L, order, n_ops, D, N);
     if (rc) return rc;
     if (live_slots()) return fail(BP_ESTATE, "stashes are live at the start of an iteration");
+    // an iteration orders its operations itself: forwards stay on the streams the executor gives them
+    int rc_w = wait_forward();
+    if (rc_w) return rc_w;
+    struct AheadOff {
+        Stage* s; bool was;
+        ~AheadOff() { s->forward_ahead = was; }
+    } ahead_off{this, forward_ahead};
+    forward_ahead = false;
 
     const size_t TH = (size_t)T * H, THb = TH * esz;
     if (sched_n < N) {

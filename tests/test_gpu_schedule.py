@@ -12,7 +12,7 @@ from tests import harness as hz
 pytestmark = pytest.mark.gpu
 
 
-def _run_iteration(cfg, D, order_tuples=None, seed=0, expect_tol=None, layout=None):
+def _run_iteration(cfg, D, order_tuples=None, seed=0, expect_tol=None, layout=None, forward_ahead=0):
     import paper_2410_19367_amd as bp
     N = cfg.n_micro
     params = si.make_params(cfg, seed, ln_jitter=0.1)
@@ -23,7 +23,7 @@ def _run_iteration(cfg, D, order_tuples=None, seed=0, expect_tol=None, layout=No
         lens = np.stack([si.make_seqlens(cfg, m, seed) for m in range(N)])
     orc = hz.make_oracle(cfg, params)
     loss_ref, G, _ = orc.full_batch_reference(inputs, targets, lens)
-    with hz.GpuStage(cfg) as g:
+    with hz.GpuStage(cfg, forward_ahead=forward_ahead) as g:
         g.load_params(params)
         if lens is not None:
             for m in range(N):
@@ -52,6 +52,17 @@ def _run_iteration(cfg, D, order_tuples=None, seed=0, expect_tol=None, layout=No
 def test_v_schedule_iteration_fp32_D2():
     cfg = si.scaled(si.CONFIGS[0], name="sched_f32", layers=1, n_chunks=4, n_micro=4, microbatch=1)
     _run_iteration(cfg, 2)
+
+
+def test_iteration_on_an_object_with_forward_ahead_is_the_same():
+    """bp_run_schedule orders its operations itself and leaves the object's forward stream alone: an
+    object created with bp_opts.forward_ahead gives the same loss and the same gradient bits."""
+    cfg = si.scaled(si.CONFIGS[4], name="sched_ahead", layers=1, hidden=128, heads=2, seq=128)
+    loss_a, grads_a, _ = _run_iteration(cfg, 4, forward_ahead=1)
+    loss_b, grads_b, _ = _run_iteration(cfg, 4, forward_ahead=0)
+    assert loss_a == loss_b
+    for k in grads_a:
+        assert np.array_equal(grads_a[k], grads_b[k]), k
 
 
 def test_v_schedule_iteration_bf16_D4_N8():
