@@ -1,5 +1,6 @@
-// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_16x16x32_bf16 in the 256 x 256 tiles,
-// v_mfma_f32_32x32x16_bf16 in the others; fp32 accumulation) for the
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_16x16x32_bf16 in the 256 x 256 tiles and in the
+// forward / data-gradient form of the smaller ones, v_mfma_f32_32x32x16_bf16 elsewhere; fp32
+// accumulation) for the
 // three shapes of a linear layer: forward Y = X W (+b)(+res), dgrad dX = dY W^T, wgrad dW += X^T dY.
 //
 // A block computes a BM x BN tile of C, stepping over K in slices of BK = 64.  Each slice of
@@ -13,8 +14,10 @@
 // Both layouts XOR-swizzle the chunk index so fragment reads spread over all LDS banks.
 // Two kernels: gemm_mfma_kernel stages slices through registers with predication (ragged shapes);
 // gemm_dma_kernel (further down) loads them straight into LDS and carries the fused epilogues,
-// split-K and multi-segment contractions.  Two LDS stages each: slice k+1 lands while slice k
-// feeds the MFMAs, one barrier per slice.
+// split-K and multi-segment contractions.  Slices land in LDS while earlier ones feed the MFMAs,
+// one barrier per slice: two LDS stages in gemm_mfma_kernel and in the large tiles of
+// gemm_dma_kernel, three in its 128 x 128 forward / data-gradient form, a ring of five half-slices
+// in its weight-gradient form.
 #include <cstdlib>
 #include <type_traits>
 
