@@ -45,6 +45,64 @@ def test_forward_ahead_small_stages(stash_recompute, wgrad_group, causal):
                           stash_recompute=stash_recompute, wgrad_group=wgrad_group)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_forward_ahead_any_lead_gives_the_same_bits(seed):
+    """Forwards up to three micro-batches ahead of the backwards, in a random but valid interleaving
+    (backwards in micro-batch order, so the weight-gradient groups form the same way), three iterations
+    on one object so that stash slots and group buffers are reused across the streams: every output and
+    gradient equals, bit for bit, what the same object type gives in the plain order on one stream."""
+    import torch
+    rng = np.random.default_rng(seed)
+    kw = [dict(layers=2, hidden=256, heads=4, seq=128, microbatch=2, causal=True),
+          dict(layers=1, hidden=384, heads=4, seq=192, microbatch=1, causal=True),
+          dict(layers=2, hidden=256, heads=2, seq=128, microbatch=3, causal=False, len_lo=30, len_hi=128)][seed]
+    n_micro = 7
+    cfg = si.scaled(si.CONFIGS[1], name="ahead_rand", n_micro=n_micro, **kw)
+    params = si.make_params(cfg, seed, 0.1)
+    ins = [(hz.to_dev(si.make_activation(cfg, "act_in", mb, seed), cfg.dtype),
+            hz.to_dev(si.make_activation(cfg, "grad_out", mb, seed), cfg.dtype)) for mb in range(n_micro)]
+
+    def calls(lead):
+        order, f, b = [], 0, 0
+        while b < n_micro:
+            can_f = f < n_micro and f - b < lead
+            if can_f and (f == b or rng.random() < 0.6):
+                order.append(("F", f)); f += 1
+            else:
+                order.append(("B", b)); b += 1
+        return order
+
+    def run(forward_ahead, lead):
+        with hz.GpuStage(cfg, max_inflight=4, wgrad_group=[3, 0, 2][seed], stash_recompute=int(seed == 1),
+                         forward_ahead=forward_ahead) as g:
+            g.load_params(params)
+            for mb in range(n_micro):
+                lens = si.make_seqlens(cfg, mb, seed)
+                if lens is not None:
+                    g.bp.bp_stage_set_seqlens(g.h, mb, lens)
+            for it in range(3):
+                g.bp.bp_stage_zero_grad(g.h)
+                zs, dxs = {}, {}
+                for kind, mb in calls(lead):
+                    if kind == "F":
+                        zs[mb] = g.forward(0, mb, ins[mb][0])
+                    else:
+                        dxs[mb] = g.backward(0, mb, ins[mb][1])
+                g.bp.bp_stage_wait_forward(g.h)
+            torch.cuda.synchronize()
+            outs = [(hz.to_host(zs[mb]), hz.to_host(dxs[mb])) for mb in range(n_micro)]
+            grads = {(l, n): g.grad(0, l, n) for l in range(cfg.layers) for n in si.PARAM_NAMES}
+        return outs, grads
+
+    outs_a, grads_a = run(1, 3)
+    outs_b, grads_b = run(0, 1)
+    for mb in range(n_micro):
+        assert np.array_equal(outs_a[mb][0], outs_b[mb][0]), f"act_out[{mb}]"
+        assert np.array_equal(outs_a[mb][1], outs_b[mb][1]), f"grad_in[{mb}]"
+    for k in grads_a:
+        assert np.array_equal(grads_a[k], grads_b[k]), k
+
+
 def test_small_fp32_bert_padded():
     cfg = si.scaled(si.CONFIGS[0], name="small_f32_bert", causal=False, len_lo=10, len_hi=64,
                     microbatch=3, n_micro=2)
