@@ -160,6 +160,10 @@ ATTN_CASES = [
     # long enough for the eight-wave forward (two tiles per step), padded widths
     (1, 512, 2, 112, True, None),
     (1, 512, 2, 40, False, [300]),
+    # the eight-wave forward with an odd number of 64-key tiles, so that the last step holds one tile only
+    (1, 576, 2, 64, True, None),
+    (1, 704, 1, 96, True, None),
+    (1, 576, 2, 128, False, [500]),
 ]
 
 
