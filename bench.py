@@ -338,8 +338,8 @@ def cpu_baseline(cfg, params, si, np):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=None,
                     help="only this index into synth_inputs.CONFIGS (1..3: baseline stage configs; 4: whole "
                          "V-schedule iteration; 5, 6: stages of the paper's BERT-64 and GPT-96 at their own shapes); "
@@ -402,8 +402,9 @@ def main():
     if args.config is None:
         others = {}
         for idx in (2, 3, 4, 5, 6):
-            # the large stage runs 256 ms per step: fewer steps keep the whole run within minutes
-            steps = max(2, args.steps // 2) if idx == 3 else args.steps
+            # the headline workload gets all the steps; the others half of them, the large stage (230 ms
+            # per step) a quarter, which keeps the whole run within a couple of minutes
+            steps = max(2, args.steps // 4) if idx == 3 else max(2, args.steps // 2)
             r, _ = run(idx, steps, min(args.warmup, 1) if idx == 3 else args.warmup)
             r.pop("kernels", None)
             others[si.CONFIGS[idx].name] = r
